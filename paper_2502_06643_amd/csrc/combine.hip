@@ -1,0 +1,82 @@
+// moe_combine: gate-weighted un-permute of the expert outputs (the step after
+// the second all-to-all in the paper's Fig. 2b).
+//
+// Gather form: one thread owns one 16-byte unit of an output row y[t] and walks
+// the token's k routes in ascending j, so the fp32 sum has a fixed order and no
+// atomics are needed.  Routes whose expert is not on local_gpu are skipped;
+// a token with no local route writes zeros.
+#include "common.h"
+
+namespace moe {
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+
+// two fp32 -> packed bf16 pair, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+    ua += 0x7FFFu + ((ua >> 16) & 1u);
+    ub += 0x7FFFu + ((ub >> 16) & 1u);
+    return (ua >> 16) | (ub & 0xFFFF0000u);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ ffn_out, const int32_t* __restrict__ inv_perm,
+                                                      const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
+                                                      const int32_t* __restrict__ placement, int local_gpu,
+                                                      long long total_units, int units_per_row, int E, int k, int N,
+                                                      uint4* __restrict__ y) {
+    const long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (u >= total_units) return;
+    const long long t = u / units_per_row;
+    const int c = (int)(u - t * units_per_row);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < k; ++j) {
+        const long long r = t * k + j;
+        if (local_gpu >= 0) {
+            const int e = topk_idx[r];
+            if ((unsigned)e >= (unsigned)E || placement[e] != local_gpu) continue;
+        }
+        const int p = inv_perm[r];
+        if ((unsigned)p >= (unsigned)N) continue;
+        const float w = topk_w[r];
+        const uint4 v = ffn_out[(long long)p * units_per_row + c];
+        if (BF16) {
+            acc[0] = fmaf(w, bf16_lo(v.x), acc[0]); acc[1] = fmaf(w, bf16_hi(v.x), acc[1]);
+            acc[2] = fmaf(w, bf16_lo(v.y), acc[2]); acc[3] = fmaf(w, bf16_hi(v.y), acc[3]);
+            acc[4] = fmaf(w, bf16_lo(v.z), acc[4]); acc[5] = fmaf(w, bf16_hi(v.z), acc[5]);
+            acc[6] = fmaf(w, bf16_lo(v.w), acc[6]); acc[7] = fmaf(w, bf16_hi(v.w), acc[7]);
+        } else {
+            acc[0] = fmaf(w, __uint_as_float(v.x), acc[0]); acc[1] = fmaf(w, __uint_as_float(v.y), acc[1]);
+            acc[2] = fmaf(w, __uint_as_float(v.z), acc[2]); acc[3] = fmaf(w, __uint_as_float(v.w), acc[3]);
+        }
+    }
+    uint4 o;
+    if (BF16) {
+        o.x = pack_bf16(acc[0], acc[1]); o.y = pack_bf16(acc[2], acc[3]);
+        o.z = pack_bf16(acc[4], acc[5]); o.w = pack_bf16(acc[6], acc[7]);
+    } else {
+        o.x = __float_as_uint(acc[0]); o.y = __float_as_uint(acc[1]);
+        o.z = __float_as_uint(acc[2]); o.w = __float_as_uint(acc[3]);
+    }
+    y[u] = o;
+}
+
+int launch_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm, const int32_t* topk_idx,
+                   const float* topk_w, const int32_t* placement, int local_gpu, int T, int d, int E, int k,
+                   void* y, hipStream_t s) {
+    const int units_per_row = d * elt_bytes(dt) / 16;
+    const long long total_units = (long long)T * units_per_row;
+    const long long grid = (total_units + 255) / 256;
+    if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_combine: T*d too large for one launch");
+    LaunchTimer timer(MOE_K_COMBINE, s);
+    if (dt == MOE_BF16)
+        hipLaunchKernelGGL(combine_kernel<true>, dim3((unsigned)grid), dim3(256), 0, s, (const uint4*)ffn_out, inv_perm, topk_idx,
+                           topk_w, placement, local_gpu, total_units, units_per_row, E, k, T * k, (uint4*)y);
+    else
+        hipLaunchKernelGGL(combine_kernel<false>, dim3((unsigned)grid), dim3(256), 0, s, (const uint4*)ffn_out, inv_perm, topk_idx,
+                           topk_w, placement, local_gpu, total_units, units_per_row, E, k, T * k, (uint4*)y);
+    return check_launch("moe_combine launch");
+}
+
+}  // namespace moe

@@ -1,0 +1,68 @@
+// Internal helpers shared by the HIP sources of libmoetuner_hip (not part of
+// the public interface, which is include/moetuner.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "moetuner.h"
+
+namespace moe {
+
+// printf-style message for moe_last_error(); returns `code` for tail calls.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+int hip_fail(hipError_t e, const char* what);
+
+// Brackets one kernel launch with a pair of events when a timing session has
+// selected this kernel id; otherwise does nothing.
+class LaunchTimer {
+public:
+    LaunchTimer(int kernel_id, hipStream_t stream);
+    ~LaunchTimer();
+    LaunchTimer(const LaunchTimer&) = delete;
+    LaunchTimer& operator=(const LaunchTimer&) = delete;
+private:
+    int slot_;
+    hipStream_t stream_;
+};
+
+inline int check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? MOE_OK : hip_fail(e, what);
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int elt_bytes(moe_dtype_t dt) { return dt == MOE_BF16 ? 2 : 4; }
+
+// ---- launchers implemented in the .hip files --------------------------------
+int launch_gate(const float* logits, int T, int E, int k, int32_t* idx, float* w, hipStream_t s);
+
+constexpr int kDispatchBlock = 256;
+constexpr int kDispatchItems = 4;
+constexpr int kDispatchChunk = kDispatchBlock * kDispatchItems;   // routes per workgroup
+int launch_dispatch(const void* x, int row_bytes, const int32_t* topk_idx, int T, int E, int k,
+                    const int32_t* placement, int G, void* send_buf, int32_t* perm, int32_t* inv_perm,
+                    int32_t* expert_counts, int32_t* expert_start, int32_t* gpu_counts,
+                    int32_t* gpu_offsets, int32_t* block_counts, hipStream_t s);
+
+int launch_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm, const int32_t* topk_idx,
+                   const float* topk_w, const int32_t* placement, int local_gpu, int T, int d, int E, int k,
+                   void* y, hipStream_t s);
+
+int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_l, int k_l1, int E_l,
+                      int E_l1, int64_t* R, hipStream_t s);
+
+// FFN: the workspace starts with a small plan area, followed by H [N,f].
+constexpr size_t kPlanBytes = 8192;
+size_t packed_bytes_f32(int E, int d, int f);
+size_t packed_bytes_bf16(int E, int d, int f);
+int launch_pack_f32(const float* w1, const float* w3, const float* w2, int E, int d, int f, float* packed, hipStream_t s);
+int launch_pack_bf16(const void* w1, const void* w3, const void* w2, int E, int d, int f, void* packed, hipStream_t s);
+int launch_ffn_f32(const float* a, int N, int d, int f, int E, const float* packed, const int32_t* counts,
+                   const int32_t* starts, const int32_t* placement, int local_gpu, float* out,
+                   int32_t* plan, float* H, hipStream_t s);
+int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
+                    const int32_t* starts, const int32_t* placement, int local_gpu, void* out,
+                    int32_t* plan, void* H, hipStream_t s);
+
+}  // namespace moe

@@ -1,0 +1,202 @@
+// moe_dispatch: placement-aware token dispatch (paper Section 1, Section 2.2,
+// Section 3.1) as a stable counting sort of the N = T*k routes by the key
+// (placement[expert], expert), followed by the row copy into the send buffer.
+//
+//   count : each workgroup histograms its contiguous chunk of routes by expert
+//   scan  : one workgroup turns the per-chunk histograms into exclusive
+//           per-expert prefixes, sums them to expert_counts (= P_{e,l}), ranks
+//           the experts by (gpu, expert) to get expert_start, and derives
+//           gpu_counts / gpu_offsets
+//   rank  : each workgroup recomputes, wavefront by wavefront, the stable rank
+//           of every route among the routes of the same expert (ballot match +
+//           popcount of the lower lanes) and writes perm / inv_perm
+//   rows  : every 16-byte piece of x[t] is read once and written to the k
+//           sorted positions of token t
+//
+// The result does not depend on how workgroups are scheduled: every position
+// is a pure function of the route id.
+#include "common.h"
+
+namespace moe {
+
+constexpr int kWaves = kDispatchBlock / 64;
+constexpr int kRoutesPerWave = 64 * kDispatchItems;
+
+__global__ __launch_bounds__(kDispatchBlock) void dispatch_count_kernel(const int32_t* __restrict__ topk_idx, int N, int E,
+                                                                        int32_t* __restrict__ block_counts) {
+    __shared__ int hist[MOE_MAX_EXPERTS];
+    for (int e = threadIdx.x; e < E; e += kDispatchBlock) hist[e] = 0;
+    __syncthreads();
+    const long long base = (long long)blockIdx.x * kDispatchChunk;
+#pragma unroll
+    for (int i = 0; i < kDispatchItems; ++i) {
+        const long long r = base + i * kDispatchBlock + threadIdx.x;
+        if (r < N) {
+            const int e = topk_idx[r];
+            if ((unsigned)e < (unsigned)E) atomicAdd(&hist[e], 1);
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kDispatchBlock) block_counts[(size_t)blockIdx.x * E + e] = hist[e];
+}
+
+__global__ __launch_bounds__(256) void dispatch_scan_kernel(int32_t* __restrict__ block_counts, int nblocks, int E,
+                                                            const int32_t* __restrict__ placement, int G,
+                                                            int32_t* __restrict__ expert_counts,
+                                                            int32_t* __restrict__ expert_start,
+                                                            int32_t* __restrict__ gpu_counts,
+                                                            int32_t* __restrict__ gpu_offsets) {
+    __shared__ int pl[MOE_MAX_EXPERTS];
+    __shared__ int tot[MOE_MAX_EXPERTS];
+    const int e = threadIdx.x;
+    if (e < E) {
+        pl[e] = placement[e];
+        int run = 0;
+        for (int b = 0; b < nblocks; ++b) {
+            const int c = block_counts[(size_t)b * E + e];
+            block_counts[(size_t)b * E + e] = run;      // exclusive prefix over chunks, per expert
+            run += c;
+        }
+        tot[e] = run;
+        expert_counts[e] = run;
+    }
+    __syncthreads();
+    if (e < E) {
+        int start = 0;
+        const int ge = pl[e];
+        for (int o = 0; o < E; ++o) {
+            const int go = pl[o];
+            if (go < ge || (go == ge && o < e)) start += tot[o];
+        }
+        expert_start[e] = start;
+    }
+    for (int g = threadIdx.x; g < G; g += 256) {
+        int cnt = 0, off = 0;
+        for (int o = 0; o < E; ++o) {
+            const int go = pl[o];
+            if (go == g) cnt += tot[o];
+            else if (go >= 0 && go < g) off += tot[o];
+        }
+        gpu_counts[g] = cnt;
+        gpu_offsets[g] = off;
+        if (g == G - 1) gpu_offsets[G] = off + cnt;
+    }
+}
+
+// lanes of this wavefront that hold the same expert as the calling lane
+__device__ __forceinline__ unsigned long long match_expert(int e, bool valid, int ebits) {
+    unsigned long long m = __ballot(valid);
+    for (int b = 0; b < ebits; ++b) {
+        const bool bit = (e >> b) & 1;
+        const unsigned long long v = __ballot(bit);
+        m &= bit ? v : ~v;
+    }
+    return m;
+}
+
+__global__ __launch_bounds__(kDispatchBlock) void dispatch_rank_kernel(const int32_t* __restrict__ topk_idx, int N, int E, int ebits,
+                                                                       const int32_t* __restrict__ block_counts,
+                                                                       const int32_t* __restrict__ expert_start,
+                                                                       int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
+    // per wavefront: first the number of routes of each expert in its slice,
+    // then (after the prefix over wavefronts) the running write offset
+    __shared__ int woff[kWaves][MOE_MAX_EXPERTS];
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    for (int i = threadIdx.x; i < kWaves * MOE_MAX_EXPERTS; i += kDispatchBlock) (&woff[0][0])[i] = 0;
+    __syncthreads();
+
+    const long long wbase = (long long)blockIdx.x * kDispatchChunk + (long long)wave * kRoutesPerWave;
+    int ex[kDispatchItems];
+    bool ok[kDispatchItems];
+    const unsigned long long lower = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int i = 0; i < kDispatchItems; ++i) {
+        const long long r = wbase + i * 64 + lane;
+        ex[i] = (r < N) ? topk_idx[r] : -1;
+        ok[i] = (unsigned)ex[i] < (unsigned)E;
+        const unsigned long long m = match_expert(ex[i], ok[i], ebits);
+        if (ok[i] && (m & lower) == 0ull) atomicAdd(&woff[wave][ex[i]], __popcll(m));   // first lane of the group
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kDispatchBlock) {
+        int run = expert_start[e] + block_counts[(size_t)blockIdx.x * E + e];
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const int c = woff[w][e];
+            woff[w][e] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    volatile int* my = woff[wave];
+#pragma unroll
+    for (int i = 0; i < kDispatchItems; ++i) {
+        const long long r = wbase + i * 64 + lane;
+        const unsigned long long m = match_expert(ex[i], ok[i], ebits);
+        int pos = 0;
+        if (ok[i]) pos = my[ex[i]] + __popcll(m & lower);
+        __builtin_amdgcn_wave_barrier();
+        if (ok[i] && (m & lower) == 0ull) my[ex[i]] += __popcll(m);
+        __builtin_amdgcn_wave_barrier();
+        if (ok[i]) {
+            perm[pos] = (int32_t)r;
+            inv_perm[r] = pos;
+        }
+    }
+}
+
+// One thread per 16-byte unit of a source row: read once, write k times.
+__global__ __launch_bounds__(256) void dispatch_rows_kernel(const uint4* __restrict__ x, long long total_units, int units_per_row,
+                                                            int k, int N, const int32_t* __restrict__ inv_perm,
+                                                            uint4* __restrict__ send_buf) {
+    const long long u = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (u >= total_units) return;
+    const long long t = u / units_per_row;
+    const int c = (int)(u - t * units_per_row);
+    const uint4 v = x[u];
+    for (int j = 0; j < k; ++j) {
+        const int p = inv_perm[t * k + j];
+        if ((unsigned)p < (unsigned)N) send_buf[(long long)p * units_per_row + c] = v;
+    }
+}
+
+int launch_dispatch(const void* x, int row_bytes, const int32_t* topk_idx, int T, int E, int k,
+                    const int32_t* placement, int G, void* send_buf, int32_t* perm, int32_t* inv_perm,
+                    int32_t* expert_counts, int32_t* expert_start, int32_t* gpu_counts,
+                    int32_t* gpu_offsets, int32_t* block_counts, hipStream_t s) {
+    const int N = T * k;
+    const int nblocks = (N + kDispatchChunk - 1) / kDispatchChunk;
+    int ebits = 0;
+    while ((1 << ebits) < E) ++ebits;
+    int rc;
+    if (nblocks > 0) {
+        LaunchTimer timer(MOE_K_DISPATCH_COUNT, s);
+        hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, block_counts);
+        if ((rc = check_launch("moe_dispatch count launch")) != MOE_OK) return rc;
+    }
+    {
+        LaunchTimer timer(MOE_K_DISPATCH_SCAN, s);
+        hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(256), 0, s, block_counts, nblocks, E, placement, G,
+                           expert_counts, expert_start, gpu_counts, gpu_offsets);
+        if ((rc = check_launch("moe_dispatch scan launch")) != MOE_OK) return rc;
+    }
+    if (nblocks > 0) {
+        LaunchTimer timer(MOE_K_DISPATCH_RANK, s);
+        hipLaunchKernelGGL(dispatch_rank_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, ebits,
+                           block_counts, expert_start, perm, inv_perm);
+        if ((rc = check_launch("moe_dispatch rank launch")) != MOE_OK) return rc;
+    }
+    if (x != nullptr && N > 0) {
+        const int units_per_row = row_bytes / 16;
+        const long long total_units = (long long)T * units_per_row;
+        const long long grid = (total_units + 255) / 256;
+        if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_dispatch: T*d too large for one launch");
+        LaunchTimer timer(MOE_K_DISPATCH_ROWS, s);
+        hipLaunchKernelGGL(dispatch_rows_kernel, dim3((unsigned)grid), dim3(256), 0, s, (const uint4*)x, total_units,
+                           units_per_row, k, N, inv_perm, (uint4*)send_buf);
+        if ((rc = check_launch("moe_dispatch rows launch")) != MOE_OK) return rc;
+    }
+    return MOE_OK;
+}
+
+}  // namespace moe

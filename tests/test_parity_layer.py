@@ -1,0 +1,158 @@
+"""GPU parity of the whole hot path (gate -> dispatch -> expert FFN -> combine,
+plus transition counts) on the benchmark configurations, in the launch
+configuration the benchmark times.
+
+Small configs are compared element by element against the full oracle.  At the
+Mixtral-shaped sizes the fp64 FFN is out of reach, so integer outputs are
+compared in full and float outputs on a seeded sample of bucket rows (first,
+last and random rows of every resident expert) and on the tokens all of whose
+local routes were sampled.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2502_06643_amd import synth
+from paper_2502_06643_amd.layer import MoELayer, to_device, to_host
+from util import TOL_BF16, TOL_F32, as_f64, fro_err, rel_err
+
+pytestmark = pytest.mark.gpu
+
+INT_OUTPUTS = ("perm", "inv_perm", "expert_counts", "expert_start", "gpu_counts", "gpu_offsets")
+
+
+def run_gpu_layer(cfg, x, lg, weights, pl, local_gpu):
+    L = MoELayer(cfg.T, cfg.d, cfg.f, cfg.E, cfg.k, cfg.G, local_gpu, cfg.dtype)
+    L.set_placement(pl)
+    L.set_weights(*weights)
+    L.forward(to_device(x), torch.from_numpy(lg).cuda())
+    torch.cuda.synchronize()
+    return L
+
+
+def check_ints(L, ref):
+    np.testing.assert_array_equal(L.topk_idx.cpu().numpy(), ref["topk_idx"])
+    for n in INT_OUTPUTS:
+        np.testing.assert_array_equal(getattr(L, n).cpu().numpy(), ref[n], err_msg=n)
+    np.testing.assert_array_equal(to_host(L.send_buf), ref["send_buf"])
+    gw = L.topk_w.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(gw - ref["topk_w"]) / np.maximum(ref["topk_w"], 1e-30)) <= 1e-4
+
+
+@pytest.mark.parametrize("name", ["c1", "c1b"])
+@pytest.mark.parametrize("map_kind,local_gpu", [("contiguous", 0), ("contiguous", 3), ("interleaved", 1),
+                                                ("uneven_1124", 3), ("uneven_1124", 0), ("contiguous", -1)])
+def test_tiny_fp32_layer_full_oracle(lib, name, map_kind, local_gpu):
+    cfg = synth.config(name)
+    x = synth.make_x(cfg)
+    lg = synth.make_logits(cfg, x)
+    weights = synth.make_expert_weights(cfg)
+    pl = {"contiguous": synth.placement_contiguous(8, 4),
+          "interleaved": np.array([3, 0, 2, 1, 0, 3, 1, 2], dtype=np.int32),
+          "uneven_1124": synth.placement_from_sizes((1, 1, 2, 4), seed=7)}[map_kind]
+    ref = O.moe_layer(x, lg, cfg.k, *weights, pl, cfg.G, local_gpu)
+    L = run_gpu_layer(cfg, x, lg, weights, pl, local_gpu)
+    check_ints(L, ref)
+    e_sorted = ref["topk_idx"].reshape(-1)[ref["perm"]]
+    is_local = np.ones(cfg.T * cfg.k, dtype=bool) if local_gpu < 0 else (pl[e_sorted] == local_gpu)
+    if is_local.any():
+        assert rel_err(L.ffn_out.cpu().numpy()[is_local], ref["ffn_out"][is_local]) <= TOL_F32
+    assert rel_err(L.y.cpu().numpy(), ref["y"]) <= TOL_F32
+    assert fro_err(L.y.cpu().numpy(), ref["y"]) <= TOL_F32
+
+
+def sample_positions(ref, pl, local_gpu, per_expert, seed):
+    """First, last and random rows of every resident expert's bucket."""
+    rng = np.random.default_rng(seed)
+    pos = []
+    for e in range(len(pl)):
+        if local_gpu >= 0 and pl[e] != local_gpu:
+            continue
+        s, c = int(ref["expert_start"][e]), int(ref["expert_counts"][e])
+        if c == 0:
+            continue
+        pick = {s, s + c - 1}
+        pick.update((s + rng.integers(0, c, min(per_expert, c))).tolist())
+        pos.extend(sorted(pick))
+    return np.array(pos, dtype=np.int64)
+
+
+def check_sampled_layer(cfg, L, x, lg, weights, pl, local_gpu, per_expert=24, seed=0):
+    idx, w = O.topk_gate(lg, cfg.k)
+    ref = O.dispatch(x, idx, pl, cfg.G)
+    ref.update(topk_idx=idx, topk_w=w)
+    check_ints(L, ref)
+    # tokens whose every local route is sampled: take tokens first, then add their routes
+    pos = sample_positions(ref, pl, local_gpu, per_expert, seed)
+    rng = np.random.default_rng(seed + 1)
+    tokens = rng.choice(cfg.T, size=min(16, cfg.T), replace=False)
+    tok_routes = (tokens[:, None] * cfg.k + np.arange(cfg.k)[None, :]).reshape(-1)
+    if local_gpu >= 0:
+        tok_routes = tok_routes[pl[idx.reshape(-1)[tok_routes]] == local_gpu]
+    pos = np.unique(np.concatenate([pos, ref["inv_perm"][tok_routes].astype(np.int64)]))
+    o_ref = O.expert_ffn_grouped(ref["send_buf"], *weights, ref["expert_counts"], ref["expert_start"], pl, local_gpu, positions=pos)
+    o_gpu = as_f64(to_host(L.ffn_out[torch.from_numpy(pos).cuda()]))
+    tol = TOL_BF16 if cfg.dtype == "bf16" else TOL_F32
+    assert rel_err(o_gpu, o_ref[pos]) <= tol
+    assert fro_err(o_gpu, o_ref[pos]) <= tol
+    y_gpu = as_f64(to_host(L.y[torch.from_numpy(tokens).cuda()]))
+    # combine as a stage: same inputs on both sides (the GPU's own expert outputs and fp32 gate weights)
+    o_bits = np.zeros((cfg.T * cfg.k, cfg.d), dtype=np.uint16 if cfg.dtype == "bf16" else np.float32)
+    o_bits[pos] = to_host(L.ffn_out[torch.from_numpy(pos).cuda()])
+    y_stage = O.combine(o_bits, ref["inv_perm"], idx, L.topk_w.cpu().numpy(), pl, local_gpu)[tokens]
+    assert rel_err(y_gpu, y_stage) <= tol
+    # end to end against the all-fp64 layer: two bf16 roundings (expert output, then y) compound, so the
+    # element-wise maximum gets twice the single-stage allowance; the Frobenius error keeps the single one
+    y_ref = O.combine(o_ref, ref["inv_perm"], idx, w, pl, local_gpu)[tokens]
+    assert fro_err(y_gpu, y_ref) <= tol
+    assert rel_err(y_gpu, y_ref) <= 2 * tol
+    return ref
+
+
+@pytest.mark.parametrize("name", ["c2", "c2b", "c3", "c4"])
+def test_bf16_configs_full_size_sampled(lib, name):
+    cfg = synth.config(name)
+    x = synth.make_x(cfg)
+    lg = synth.make_logits(cfg, x)
+    weights = synth.make_expert_weights(cfg)
+    pl = synth.make_placement(cfg)
+    L = run_gpu_layer(cfg, x, lg, weights, pl, cfg.local_gpu)
+    ref = check_sampled_layer(cfg, L, x, lg, weights, pl, cfg.local_gpu)
+    share = ref["expert_counts"].max() / ref["expert_counts"].sum()
+    print(f"{name}: largest expert holds {share:.3f} of the routes; gpu_counts {ref['gpu_counts'].tolist()}")
+
+
+def test_c5_chained_layers_and_transition_counts(lib):
+    """Four Mixtral-shaped layers.  Router logits of every layer come from the
+    seeded layer-0 activations (plus the successor bonus keyed on the previous
+    layer's top-1 expert), so both sides see identical logits; activations flow
+    layer to layer on the GPU, and each layer's floats are checked with the
+    GPU's own bf16 input of that layer handed to the oracle (teacher forcing)."""
+    cfg = synth.config("c5")
+    x0 = synth.make_x(cfg)
+    pl = synth.make_placement(cfg)
+    L = MoELayer(cfg.T, cfg.d, cfg.f, cfg.E, cfg.k, cfg.G, cfg.local_gpu, cfg.dtype)
+    L.set_placement(pl)
+    x_dev = to_device(x0)
+    prev_idx_dev, prev_idx_ref, prev_top1 = None, None, None
+    affinity = []
+    for layer in range(cfg.layers):
+        lg = synth.make_logits(cfg, x0, layer, prev_top1)
+        weights = synth.make_expert_weights(cfg, layer)
+        L.set_weights(*weights)
+        x_host = to_host(x_dev)
+        L.forward(x_dev, torch.from_numpy(lg).cuda())
+        torch.cuda.synchronize()
+        ref = check_sampled_layer(cfg, L, x_host, lg, weights, pl, cfg.local_gpu, per_expert=6, seed=layer)
+        if layer > 0:
+            R = torch.zeros((cfg.E, cfg.E), dtype=torch.int64, device="cuda")
+            lib.moe_transition_counts(prev_idx_dev, L.topk_idx, cfg.T, cfg.k, cfg.k, cfg.E, cfg.E, R)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(R.cpu().numpy(), O.transition_counts(prev_idx_ref, ref["topk_idx"], cfg.E, cfg.E))
+            succ = synth.successors(cfg.seed(layer - 1), cfg.E)
+            affinity.append(float(np.mean([ref["topk_idx"][t, 0] in succ[prev_top1[t]] for t in range(0, cfg.T, 16)])))
+        prev_idx_dev, prev_idx_ref, prev_top1 = L.topk_idx.clone(), ref["topk_idx"], ref["topk_idx"][:, 0]
+        x_dev = L.y.clone()
+        del weights
+    print("c5: fraction of tokens whose next-layer top-1 is a successor expert:", affinity)

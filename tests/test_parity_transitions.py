@@ -1,0 +1,49 @@
+"""GPU parity: moe_transition_counts vs the oracle, bit exact (int64)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2502_06643_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def run(lib, a, b, E1, E2, R0=None):
+    R = torch.zeros((E1, E2), dtype=torch.int64, device="cuda") if R0 is None else torch.from_numpy(R0).cuda()
+    lib.moe_transition_counts(torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda(), a.shape[0], a.shape[1], b.shape[1], E1, E2, R)
+    torch.cuda.synchronize()
+    return R.cpu().numpy()
+
+
+@pytest.mark.parametrize("T,E1,E2,k1,k2", [(1, 8, 8, 2, 2), (1000, 8, 8, 2, 2), (16384, 8, 8, 2, 2), (5000, 64, 64, 6, 6),
+                                           (3000, 5, 9, 1, 3), (2000, 200, 100, 4, 2), (777, 256, 256, 16, 16), (4097, 16, 4, 6, 2)])
+def test_matches_oracle(lib, T, E1, E2, k1, k2):
+    a = synth.random_topk_idx(T, T, E1, k1)
+    b = synth.random_topk_idx(T + 1, T, E2, k2)
+    np.testing.assert_array_equal(run(lib, a, b, E1, E2), O.transition_counts(a, b, E1, E2))
+
+
+def test_accumulates_over_batches_and_large_start_values(lib):
+    a = synth.random_topk_idx(1, 3000, 8, 2)
+    b = synth.random_topk_idx(2, 3000, 8, 2)
+    R0 = np.full((8, 8), (1 << 40) + 3, dtype=np.int64)          # beyond 32 bits: the table really is int64
+    ref = O.transition_counts(a, b, 8, 8, R0.copy())
+    got = run(lib, a, b, 8, 8, R0.copy())
+    np.testing.assert_array_equal(got, ref)
+    got2 = run(lib, a, b, 8, 8, got.copy())
+    np.testing.assert_array_equal(got2 - got, got - R0)
+
+
+def test_marginals_at_a_size_the_oracle_loop_would_crawl_through(lib):
+    T, E, k = 1 << 20, 8, 2
+    a = synth.random_topk_idx(3, T, E, k)
+    b = synth.random_topk_idx(4, T, E, k)
+    R = run(lib, a, b, E, E)
+    np.testing.assert_array_equal(R.sum(axis=1), k * np.bincount(a.reshape(-1), minlength=E))
+    np.testing.assert_array_equal(R.sum(axis=0), k * np.bincount(b.reshape(-1), minlength=E))
+    assert R.sum() == T * k * k
+    # sampled bins one by one
+    for e1, e2 in [(0, 0), (3, 5), (7, 1)]:
+        n = int(((a == e1).any(axis=1) & (b == e2).any(axis=1)).sum())
+        assert R[e1, e2] == n
