@@ -3,15 +3,22 @@ import numpy as np
 
 
 def rel_err(got, ref):
-    """max_i |got_i - ref_i| / max(|ref_i|, rms(ref)): a relative error that
-    does not blow up on outputs that happen to be near zero."""
-    got = np.asarray(got, dtype=np.float64)
-    ref = np.asarray(ref, dtype=np.float64)
+    """max_ij |got_ij - ref_ij| / max(|ref_ij|, rms(ref_i,:)).
+
+    A relative error that does not blow up on outputs that happen to be near
+    zero: an element is measured against its own magnitude or, if it is smaller
+    than that, against the root-mean-square of its row.  The row is the right
+    scale because every element of a row is a dot product with the same
+    activation vector, so rounding errors grow with that row's magnitude, and
+    rows of one batch can differ by orders of magnitude.  1-D inputs are one
+    row."""
+    got = np.atleast_2d(np.asarray(got, dtype=np.float64))
+    ref = np.atleast_2d(np.asarray(ref, dtype=np.float64))
     if ref.size == 0:
         return 0.0
-    rms = float(np.sqrt(np.mean(ref * ref)))
-    den = np.maximum(np.abs(ref), rms if rms > 0 else 1.0)
-    return float(np.max(np.abs(got - ref) / den))
+    rms = np.sqrt(np.mean(ref * ref, axis=-1, keepdims=True))
+    rms = np.where(rms > 0, rms, 1.0)
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rms)))
 
 
 def fro_err(got, ref):
