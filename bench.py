@@ -33,7 +33,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
-def cpu_baseline(cfg, x, lg, weights, pl, budget_rows=2048):
+def cpu_baseline(cfg, x, lg, weights, pl, budget_rows=8192):
     """The oracle as it stands, on the host: gate and dispatch over the whole
     batch, the fp64 expert FFN on a seeded sample of bucket rows, combine on the
     tokens that own those rows; the layer time is the integer stages plus the

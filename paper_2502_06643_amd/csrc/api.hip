@@ -172,7 +172,7 @@ int moe_pack_weights(const void* w1, const void* w3, const void* w2, int E, int 
 
 size_t moe_ffn_workspace_bytes(int N, int d, int f, int E, moe_dtype_t dt) {
     if (N < 0 || check_ffn_shape("moe_ffn_workspace_bytes", E, d, f, dt) != MOE_OK) return 0;
-    return kPlanBytes + round_up((size_t)N * f * elt_bytes(dt), 256) + 256;
+    return kPlanBytes + round_up((size_t)N * f * elt_bytes(dt), 256) + 256 + (dt == MOE_BF16 ? ffn_bf16_scratch_bytes() : 0);
 }
 
 int moe_expert_ffn_grouped(const void* send_buf, moe_dtype_t dt, int N, int d, int f, int E,

@@ -56,6 +56,7 @@ int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_
 constexpr size_t kPlanBytes = 8192;
 size_t packed_bytes_f32(int E, int d, int f);
 size_t packed_bytes_bf16(int E, int d, int f);
+size_t ffn_bf16_scratch_bytes();      // fp32 partial tiles of the split tail, sized for the largest supported XCD
 int launch_pack_f32(const float* w1, const float* w3, const float* w2, int E, int d, int f, float* packed, hipStream_t s);
 int launch_pack_bf16(const void* w1, const void* w3, const void* w2, int E, int d, int f, void* packed, hipStream_t s);
 int launch_ffn_f32(const float* a, int N, int d, int f, int E, const float* packed, const int32_t* counts,

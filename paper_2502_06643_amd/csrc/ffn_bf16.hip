@@ -4,45 +4,89 @@
 //   up  : H   = silu(A W1_e) * (A W3_e)   [rows, f]  bf16, fp32 accumulate
 //   down: out = H W2_e                    [rows, d]  bf16, fp32 accumulate
 //
-// Weights are pre-packed (moe_pack_weights) in MFMA fragment order: the matrix
-// is cut into panels of 32 output columns; a panel is stored k-block after
-// k-block, one k-block being 16 reduction steps x 32 columns = 1 KB, inside
-// which lane l of a wavefront owns 8 consecutive k of column l % 32 starting at
-// k = 8 * (l / 32).  That is exactly the B operand of
-// v_mfma_f32_32x32x16_bf16, so a tile of weights is a straight 16-byte-per-lane
-// copy from memory to LDS to registers.  For the up projection the panels of
-// W1 and W3 alternate (W1 cols 0-31, W3 cols 0-31, W1 cols 32-63, ...), so the
-// two factors of the SwiGLU product sit in the same lane and register index.
+// Work decomposition.  A workgroup of 8 wavefronts (4 along rows x 2 along
+// columns, 64 x 128 outputs each, two wavefronts per SIMD) owns one 256 x 256
+// output tile of one expert; the (expert, row tile) list comes from the
+// device-side plan, so no bucket size ever reaches the host.  Workgroup ids are
+// dealt round-robin to the 8 XCDs by the hardware; tile ids are assigned so
+// that every XCD works on a contiguous range ordered expert -> column tile ->
+// row tile: workgroups that share an L2 share weight panels and activation rows.
+// Wavefronts whose 64 rows lie entirely past the end of a ragged bucket skip the
+// matrix instructions (and leave their SIMD to the other wavefront).
 //
-// Activations stay row-major; their LDS tile is [rows][64 k] with the 16-byte
-// chunks of a row XOR-swizzled by (row >> 1) & 7, which makes both the
-// row-contiguous stores and the column-of-rows fragment loads conflict-free.
+// Weights are pre-packed (moe_pack_weights) in MFMA fragment order.  The packed
+// matrix is cut into blocks of 256 columns x 64 reduction steps = 32 KB, stored
+// column tile after column tile, k tile after k tile, so the 32 KB a workgroup
+// needs per step are contiguous.  A block holds 8 panels (32 columns) x 4
+// k-blocks (16 steps) of 1 KB, in which lane l of a wavefront owns the 8
+// consecutive k of column l % 32 that start at k = 8 * (l / 32): exactly the B
+// operand of v_mfma_f32_32x32x16_bf16.  For the up projection the panels of W1
+// and W3 alternate, so both factors of the SwiGLU product sit in the same lane
+// and accumulator index.  Activations stay row-major; their LDS tile is
+// [256 rows][64 k] with the eight 16-byte slots of a row XOR-swizzled by
+// (row >> 1) & 7, conflict-free for the fills and for the fragment reads.
 //
-// Work decomposition: a workgroup (4 wavefronts, 2 x 2) owns one BM x BN output
-// tile of one expert; the (expert, row tile) list comes from the device-side
-// plan.  Tile ids are dealt to the 8 XCDs in contiguous ranges (workgroup ids
-// round-robin over XCDs), ordered expert -> column tile -> row tile, so that
-// workgroups sharing an L2 share weight panels and activation rows.
+// Data movement.  global_load_lds_dwordx4 copies 16 bytes per lane from memory
+// straight into LDS (destination = M0 + 16 * lane, one wavefront instruction
+// fills 1 KB), so a tile needs no staging registers and no LDS store
+// instructions; the swizzle is applied by choosing which global chunk each lane
+// fetches.  Two LDS stages of 64 KB: the loads of k tile kt+1 are in flight
+// while tile kt is multiplied, and one barrier per k tile both publishes tile
+// kt and retires the stage that tile kt+1 overwrites.  The loads are issued
+// from inline assembly: the compiler then does not treat them as LDS writes
+// that every later LDS read must wait for, and the wait is explicit
+// (s_waitcnt vmcnt(0) before the barrier).
+//
+// Tail balancing (down projection).  When the last round of tiles on an XCD
+// would occupy at most half of its compute units, each of those tiles is split
+// along k into s parts that run as separate workgroups and write fp32 partial
+// accumulators; a small fix-up kernel adds the parts in a fixed order and runs
+// the normal epilogue.  Results stay bitwise reproducible.
+//
+// Epilogue.  Accumulators are converted to bf16 (round to nearest even),
+// transposed through a per-wavefront LDS staging tile and written with
+// 16-byte stores that cover whole 128-byte lines.
 #include "ffn_plan.h"
+#include <cstdlib>
 
 namespace moe {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int BK = 64;                 // reduction steps per LDS tile
+constexpr int BM = 256, BN = 256, BK = 64;      // workgroup tile and k depth of one LDS stage
+constexpr int WM = 4, WN = 2, NW = WM * WN;     // wavefront grid
+constexpr int WTM = BM / WM, WTN = BN / WN;     // 64 x 128 per wavefront
+constexpr int FM = WTM / 32, FN = WTN / 32;     // 2 x 4 fragments of 32 x 32
+constexpr int NS = 2;                           // LDS stages
+constexpr int KB = BK / 16;                     // k-blocks per stage
+constexpr int STAGE = (BM + BN) * BK;           // elements per stage
+constexpr int A_CHUNKS = BM / 8, B_CHUNKS = BN / 8;             // 1 KB pieces per stage
+constexpr int A_PER_WAVE = A_CHUNKS / NW, B_PER_WAVE = B_CHUNKS / NW;
+constexpr int LPT = A_PER_WAVE + B_PER_WAVE;    // loads per wavefront and k tile
+constexpr int kThreads = NW * 64;
 constexpr int kPanelCols = 32;
-constexpr int kNPad = 256;             // packed column count is padded to this
+constexpr int kXcds = 8;
+constexpr int kMaxSplit = 8;
+constexpr int kMinSplitKT = 16;                 // a k part is at least this many k tiles
+constexpr int kAccPerLane = FM * FN * 16;
+constexpr size_t kPartialFloats = (size_t)BM * BN;              // one fp32 partial tile
 
-static inline size_t npad13(int f) { return round_up((size_t)2 * f, kNPad); }
-static inline size_t npad2(int d) { return round_up((size_t)d, kNPad); }
+static inline size_t npad13(int f) { return round_up((size_t)2 * f, BN); }
+static inline size_t npad2(int d) { return round_up((size_t)d, BN); }
 
 size_t packed_bytes_bf16(int E, int d, int f) {
     return (size_t)E * (npad13(f) * d + npad2(d) * f) * 2;
 }
 
-// One thread per 16-byte unit of the packed buffer.
+// fp32 partial tiles for the split tail of the down projection: one slot per compute unit
+constexpr int kMaxCusPerXcd = 48;
+size_t ffn_bf16_scratch_bytes() { return (size_t)kXcds * kMaxCusPerXcd * kPartialFloats * sizeof(float); }
+
+// One thread per 16-byte unit of the packed buffer.  Unit index within one matrix of one expert:
+// (((nt * KT + kt) * 8 + panel) * 4 + kb) * 64 + lane.
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restrict__ w1, const uint16_t* __restrict__ w3,
                                                         const uint16_t* __restrict__ w2, int d, int f,
                                                         long long units13, long long units2, long long total,
@@ -52,25 +96,26 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restri
     const long long per_e = units13 + units2;
     const long long e = o / per_e;
     long long r = o - e * per_e;
+    const bool up = r < units13;
+    if (!up) r -= units13;
+    const int K = up ? d : f, ncols = up ? f : d;
+    const int KT = K / BK;
+    const int lane = (int)(r & 63);
+    const int kb = (int)((r >> 6) & 3);
+    const int p = (int)((r >> 8) & 7);
+    const long long tile = r >> 11;                 // nt * KT + kt
+    const int kt = (int)(tile % KT);
+    const long long panel = (tile / KT) * 8 + p;    // 32-column panel of the (interleaved) matrix
     const uint16_t* src;
-    int K, ncols, col;
-    if (r < units13) {
-        K = d; ncols = f;
-        const long long panel = r / ((long long)K * 4);
-        const int lane = (int)(r % 64);
+    int col;
+    if (up) {
         col = (int)(panel / 2) * kPanelCols + lane % 32;
         src = ((panel & 1) ? w3 : w1) + (size_t)e * d * f;
     } else {
-        r -= units13;
-        K = f; ncols = d;
-        const long long panel = r / ((long long)K * 4);
-        const int lane = (int)(r % 64);
         col = (int)panel * kPanelCols + lane % 32;
         src = w2 + (size_t)e * d * f;
     }
-    const int kb = (int)((r % ((long long)K * 4)) / 64);
-    const int lane = (int)(r % 64);
-    const int k0 = kb * 16 + 8 * (lane / 32);
+    const int k0 = kt * BK + kb * 16 + 8 * (lane / 32);
     uint16_t v[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] = (col < ncols) ? src[(size_t)(k0 + i) * ncols + col] : (uint16_t)0;
@@ -90,69 +135,211 @@ int launch_pack_bf16(const void* w1, const void* w3, const void* w2, int E, int 
     return check_launch("moe_pack_weights launch");
 }
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+// ---------------------------------------------------------------------------
+// which piece of work does this workgroup (or fix-up block) own?
+// ---------------------------------------------------------------------------
+struct WorkItem {
+    int expert, row0, rows, nt;
+    int kt0, kt1;        // k tile range
+    int partial;         // slot of the fp32 partial tile, or -1 for a whole tile
+    int parts;           // split factor of this tile (fix-up only)
+};
 
-template <int BM, int BN, bool UP>
-__global__ __launch_bounds__(256) void ffn_bf16_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ Wp,
-                                                       size_t expert_stride, int K, int npad, uint16_t* __restrict__ C,
-                                                       int ldc, const int32_t* __restrict__ plan) {
-    constexpr int WTM = BM / 2, WTN = BN / 2, FM = WTM / 32, FN = WTN / 32;
-    constexpr int PA = BM / 32, PB = BN / 32;       // 16-byte loads per thread and k tile
-    static_assert(!UP || (FN % 2 == 0), "SwiGLU pairs need an even number of column fragments per wavefront");
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t* As = smem;                 // [BM][64]
-    uint16_t* Bs = smem + BM * BK;       // [PB panels][4 k-blocks][64 lanes][8]
+struct XcdShare {
+    long long t_begin;   // first tile of this XCD
+    int full;            // tiles run whole
+    int tail;            // tiles run in `split` k parts each
+    int split;
+};
 
-    // ---- which tile --------------------------------------------------------
-    const int32_t* prefix = plan + (UP ? kPlanTiles0 : kPlanTiles1);
+__device__ __forceinline__ XcdShare xcd_share(long long total_tiles, int x, int KT, int cus_per_xcd, bool allow_split) {
+    XcdShare s;
+    const long long chunk = (total_tiles + kXcds - 1) / kXcds;
+    s.t_begin = (long long)x * chunk;
+    long long cnt = total_tiles - s.t_begin;
+    cnt = cnt < 0 ? 0 : (cnt > chunk ? chunk : cnt);
+    s.full = (int)cnt;
+    s.tail = 0;
+    s.split = 1;
+    if (allow_split) {
+        const int r = (int)(cnt % cus_per_xcd);
+        if (r > 0 && 2 * r <= cus_per_xcd) {
+            int sp = cus_per_xcd / r;
+            if (sp > kMaxSplit) sp = kMaxSplit;
+            while (sp > 1 && KT / sp < kMinSplitKT) --sp;
+            if (sp > 1) {
+                s.full = (int)cnt - r;
+                s.tail = r;
+                s.split = sp;
+            }
+        }
+    }
+    return s;
+}
+
+__device__ __forceinline__ void locate_tile(const int32_t* __restrict__ plan, const int32_t* __restrict__ prefix, int NT,
+                                            long long tile, WorkItem& w) {
     const int n_exp = plan[0];
-    const int NT = npad / BN;
-    const long long total = (long long)prefix[n_exp] * NT;
-    const long long chunk = (total + 7) / 8;
-    const long long slot = blockIdx.x / 8;
-    if (slot >= chunk) return;
-    const long long tile = (long long)(blockIdx.x % 8) * chunk + slot;
-    if (tile >= total) return;
     int i = 0;
     while (i + 1 < n_exp && (long long)prefix[i + 1] * NT <= tile) ++i;
     const int mt_e = prefix[i + 1] - prefix[i];
     const int rem = (int)(tile - (long long)prefix[i] * NT);
-    const int nt = rem / mt_e, mt = rem - nt * mt_e;
-    const int expert = plan[kPlanExpert + i];
-    const int row0 = plan[kPlanStart + i] + mt * BM;
-    const int rows = min(BM, plan[kPlanCount + i] - mt * BM);
+    w.nt = rem / mt_e;
+    const int mt = rem - w.nt * mt_e;
+    w.expert = plan[kPlanExpert + i];
+    w.row0 = plan[kPlanStart + i] + mt * BM;
+    w.rows = min(BM, plan[kPlanCount + i] - mt * BM);
+}
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wave_m = wave >> 1, wave_n = wave & 1;
+// ---------------------------------------------------------------------------
+// pieces of the GEMM
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
+                 :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
 
-    const uint16_t* Bt = Wp + (size_t)expert * expert_stride + (size_t)nt * PB * ((size_t)K * kPanelCols);
-    const size_t panel_stride = (size_t)K * kPanelCols;
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
-    // ---- staging registers ---------------------------------------------------
-    u32x4 ra[PA], rb[PB];
-    const int a_row = tid >> 3, a_chunk = tid & 7;
-    size_t a_off[PA];
+// acc += A[row0 .. row0+rows, k tiles kt0..kt1) * B(tile), everything through LDS
+__device__ __forceinline__ void mainloop(f32x16 (&acc)[FM][FN], uint16_t* smem, const uint16_t* __restrict__ A,
+                                         const uint16_t* __restrict__ Bbase, int K, const WorkItem& w, int wave, int lane,
+                                         bool wave_active) {
+    const int wave_m = wave / WN, wave_n = wave % WN;
+    const uint16_t* Abase = A + (size_t)w.row0 * K;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
+
+    // per-lane byte offsets of this wavefront's 1 KB pieces (the k tile moves the scalar base)
+    uint32_t a_voff[A_PER_WAVE], b_voff[B_PER_WAVE];
 #pragma unroll
-    for (int p = 0; p < PA; ++p) {
-        const int r = min(p * 32 + a_row, rows - 1);            // rows past the bucket re-read its last row
-        a_off[p] = (size_t)(row0 + r) * K + a_chunk * 8;
+    for (int j = 0; j < A_PER_WAVE; ++j) {
+        const int c = wave + j * NW;                         // rows 8c .. 8c+7
+        const int r = c * 8 + (lane >> 3);
+        const int g = swz(r, lane & 7);                      // global chunk that lands in LDS slot lane & 7
+        a_voff[j] = (uint32_t)min(r, w.rows - 1) * (uint32_t)K * 2u + (uint32_t)g * 16u;   // rows past the bucket re-read its last row
     }
-#define MOE_GLOAD(kt)                                                                                         \
-    {                                                                                                         \
-        _Pragma("unroll") for (int p = 0; p < PA; ++p)                                                        \
-            ra[p] = *reinterpret_cast<const u32x4*>(A + a_off[p] + (size_t)(kt) * BK);                        \
-        _Pragma("unroll") for (int p = 0; p < PB; ++p)                                                        \
-            rb[p] = *reinterpret_cast<const u32x4*>(Bt + p * panel_stride + (size_t)(kt) * (BK * kPanelCols) + tid * 8); \
+#pragma unroll
+    for (int j = 0; j < B_PER_WAVE; ++j) b_voff[j] = (uint32_t)(wave + j * NW) * 1024u + (uint32_t)lane * 16u;
+
+    auto issue = [&](int kt, int stage) {
+        const uint16_t* ab = Abase + (size_t)kt * BK;
+        const uint16_t* bb = Bbase + (size_t)kt * (BK * BN);
+        const uint32_t l = lds0 + (uint32_t)stage * (STAGE * 2) + (uint32_t)wave * 1024u;
+#pragma unroll
+        for (int j = 0; j < A_PER_WAVE; ++j) dma16(a_voff[j], ab, l + j * NW * 1024);
+#pragma unroll
+        for (int j = 0; j < B_PER_WAVE; ++j) dma16(b_voff[j], bb, l + (A_CHUNKS + j * NW) * 1024);
+    };
+
+    issue(w.kt0, 0);
+    int stage = 0;
+    for (int kt = w.kt0; kt < w.kt1; ++kt) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wavefront's pieces of tile kt have landed
+        __syncthreads();                                     // everyone's have, and tile kt-1 has been consumed
+        if (kt + 1 < w.kt1) issue(kt + 1, stage ^ 1);
+        if (wave_active) {
+            const uint16_t* As = smem + stage * STAGE;
+            const uint16_t* Bs = As + BM * BK;
+#pragma unroll
+            for (int ks = 0; ks < KB; ++ks) {
+                bf16x8 af[FM], bfr[FN];
+#pragma unroll
+                for (int a = 0; a < FM; ++a) {
+                    const int r = wave_m * WTM + a * 32 + (lane & 31);
+                    af[a] = *reinterpret_cast<const bf16x8*>(As + r * BK + swz(r, ks * 2 + (lane >> 5)) * 8);
+                }
+#pragma unroll
+                for (int b = 0; b < FN; ++b)
+                    bfr[b] = *reinterpret_cast<const bf16x8*>(Bs + ((wave_n * FN + b) * KB + ks) * 512 + lane * 8);
+#pragma unroll
+                for (int a = 0; a < FM; ++a)
+#pragma unroll
+                    for (int b = 0; b < FN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+            }
+        }
+        stage ^= 1;
     }
-#define MOE_LSTORE()                                                                                          \
-    {                                                                                                         \
-        _Pragma("unroll") for (int p = 0; p < PA; ++p) {                                                      \
-            const int r = p * 32 + a_row;                                                                     \
-            *reinterpret_cast<u32x4*>(As + r * BK + swz(r, a_chunk) * 8) = ra[p];                             \
-        }                                                                                                     \
-        _Pragma("unroll") for (int p = 0; p < PB; ++p)                                                        \
-            *reinterpret_cast<u32x4*>(Bs + p * (BK * kPanelCols) + tid * 8) = rb[p];                          \
+}
+
+// accumulators -> bf16 -> per-wavefront LDS staging tile -> 16-byte stores of whole lines.
+// accumulator v of a 32x32 fragment: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+template <bool UP>
+__device__ __forceinline__ void epilogue(const f32x16 (&acc)[FM][FN], uint16_t* smem, uint16_t* __restrict__ C, int ldc,
+                                         const WorkItem& w, int wave, int lane) {
+    constexpr int OUTC = UP ? WTN / 2 : WTN;          // output columns of this wavefront
+    constexpr int RS = OUTC + 8;                      // staging row stride (elements); the pad staggers the banks
+    constexpr int CPR = OUTC / 8;                     // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;                     // rows covered by one wavefront-wide 16-byte access
+    const int wave_m = wave / WN, wave_n = wave % WN;
+    uint16_t* stg = smem + wave * (WTM * RS);
+#pragma unroll
+    for (int a = 0; a < FM; ++a) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (UP) {
+#pragma unroll
+                for (int b = 0; b < FN; b += 2) {
+                    const float u = acc[a][b][v], g = acc[a][b + 1][v];
+                    const float h = u / (1.0f + __expf(-u)) * g;
+                    stg[r * RS + (b >> 1) * 32 + (lane & 31)] = __builtin_bit_cast(uint16_t, (__bf16)h);
+                }
+            } else {
+#pragma unroll
+                for (int b = 0; b < FN; ++b)
+                    stg[r * RS + b * 32 + (lane & 31)] = __builtin_bit_cast(uint16_t, (__bf16)acc[a][b][v]);
+            }
+        }
     }
+    const int col = (UP ? w.nt * (BN / 2) : w.nt * BN) + wave_n * OUTC + (lane % CPR) * 8;
+#pragma unroll
+    for (int it = 0; it < WTM / RPI; ++it) {
+        const int r = it * RPI + lane / CPR;
+        const int gr = wave_m * WTM + r;
+        if (gr < w.rows && col < ldc)
+            *reinterpret_cast<u32x4*>(C + (size_t)(w.row0 + gr) * ldc + col) =
+                *reinterpret_cast<const u32x4*>(stg + r * RS + (lane % CPR) * 8);
+    }
+}
+
+template <bool UP>
+constexpr int smem_bytes() {
+    constexpr int stage_bytes = NS * STAGE * 2;
+    constexpr int outc = UP ? WTN / 2 : WTN;
+    constexpr int epi_bytes = NW * WTM * (outc + 8) * 2;
+    return stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+}
+
+template <bool UP, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ Wp,
+                                                            size_t expert_stride, int K, int npad, uint16_t* __restrict__ C,
+                                                            int ldc, const int32_t* __restrict__ plan, float* __restrict__ partials,
+                                                            int cus_per_xcd) {
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    const int32_t* prefix = plan + (UP ? kPlanTiles0 : kPlanTiles1);
+    const int NT = npad / BN, KT = K / BK;
+    const long long total = (long long)prefix[plan[0]] * NT;
+    const int x = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const XcdShare sh = xcd_share(total, x, KT, cus_per_xcd, SPLIT);
+    if (slot >= sh.full + sh.tail * sh.split) return;
+    WorkItem w;
+    if (slot < sh.full) {
+        locate_tile(plan, prefix, NT, sh.t_begin + slot, w);
+        w.kt0 = 0; w.kt1 = KT; w.partial = -1;
+    } else {
+        const int j = slot - sh.full;
+        const int part = j % sh.split;
+        locate_tile(plan, prefix, NT, sh.t_begin + sh.full + j / sh.split, w);
+        w.kt0 = (int)((long long)part * KT / sh.split);
+        w.kt1 = (int)((long long)(part + 1) * KT / sh.split);
+        w.partial = x * cus_per_xcd + j;
+    }
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool wave_active = (wave / WN) * WTM < w.rows;
+    const uint16_t* Bbase = Wp + (size_t)w.expert * expert_stride + (size_t)w.nt * ((size_t)K * BN);
 
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -162,102 +349,136 @@ __global__ __launch_bounds__(256) void ffn_bf16_kernel(const uint16_t* __restric
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    const int KT = K / BK;
-    MOE_GLOAD(0)
-    for (int kt = 0; kt < KT; ++kt) {
-        __syncthreads();                 // everyone is done reading the previous tile
-        MOE_LSTORE()
-        __syncthreads();
-        if (kt + 1 < KT) MOE_GLOAD(kt + 1)   // in flight while the matrix cores work
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[FM], bfr[FN];
-#pragma unroll
-            for (int a = 0; a < FM; ++a) {
-                const int r = wave_m * WTM + a * 32 + (lane & 31);
-                af[a] = *reinterpret_cast<const bf16x8*>(As + r * BK + swz(r, ks * 2 + (lane >> 5)) * 8);
-            }
-#pragma unroll
-            for (int b = 0; b < FN; ++b)
-                bfr[b] = *reinterpret_cast<const bf16x8*>(Bs + (wave_n * FN + b) * (BK * kPanelCols) + ks * 512 + lane * 8);
+    mainloop(acc, smem, A, Bbase, K, w, wave, lane, wave_active);
+
+    if (SPLIT && w.partial >= 0) {
+        if (wave_active) {
+            // 16 bytes per lane and store: [fragment][quad of accumulators][thread]
+            f32x4* dst = reinterpret_cast<f32x4*>(partials + (size_t)w.partial * kPartialFloats) + tid;
 #pragma unroll
             for (int a = 0; a < FM; ++a)
 #pragma unroll
                 for (int b = 0; b < FN; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
-        }
-    }
-
-#undef MOE_GLOAD
-#undef MOE_LSTORE
-
-    // ---- epilogue ------------------------------------------------------------
-    // accumulator v of a 32x32 fragment: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
-    const int panel0 = nt * PB + wave_n * FN;
 #pragma unroll
-    for (int a = 0; a < FM; ++a) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = wave_m * WTM + a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            if (r >= rows) continue;
-            uint16_t* crow = C + (size_t)(row0 + r) * ldc;
-            if (UP) {
-#pragma unroll
-                for (int b = 0; b < FN; b += 2) {
-                    const int col = ((panel0 + b) >> 1) * kPanelCols + (lane & 31);
-                    if (col < ldc) {
-                        const float u = acc[a][b][v], g = acc[a][b + 1][v];
-                        const float h = u / (1.0f + __expf(-u)) * g;
-                        crow[col] = __builtin_bit_cast(uint16_t, (__bf16)h);
+                    for (int q = 0; q < 4; ++q) {
+                        f32x4 t = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+                        dst[(size_t)((a * FN + b) * 4 + q) * kThreads] = t;
                     }
-                }
-            } else {
-#pragma unroll
-                for (int b = 0; b < FN; ++b) {
-                    const int col = (panel0 + b) * kPanelCols + (lane & 31);
-                    if (col < ldc) crow[col] = __builtin_bit_cast(uint16_t, (__bf16)acc[a][b][v]);
-                }
-            }
         }
+        return;
     }
+    __syncthreads();                                  // the last tile's fragments have been read by everyone
+    if (wave_active) epilogue<UP>(acc, smem, C, ldc, w, wave, lane);
 }
 
-template <int BM, int BN, bool UP>
-static int launch_gemm(const uint16_t* A, const uint16_t* Wp, size_t expert_stride, int K, int npad, uint16_t* C, int ldc,
-                       const int32_t* plan, int mt_max, hipStream_t s) {
-    constexpr int smem = (BM + BN) * BK * 2;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_bf16_kernel<BM, BN, UP>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute");
-        configured = true;
+// adds the k parts of the split tail tiles in part order and writes the tiles
+__global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npad, uint16_t* __restrict__ C, int ldc,
+                                                                  const int32_t* __restrict__ plan,
+                                                                  const float* __restrict__ partials, int cus_per_xcd) {
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    const int32_t* prefix = plan + kPlanTiles1;
+    const int NT = npad / BN, KT = K / BK;
+    const long long total = (long long)prefix[plan[0]] * NT;
+    const int x = blockIdx.x % kXcds, q = blockIdx.x / kXcds;
+    const XcdShare sh = xcd_share(total, x, KT, cus_per_xcd, true);
+    if (q >= sh.tail) return;
+    WorkItem w;
+    locate_tile(plan, prefix, NT, sh.t_begin + sh.full + q, w);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if ((wave / WN) * WTM >= w.rows) return;
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    for (int part = 0; part < sh.split; ++part) {
+        const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * cus_per_xcd + q * sh.split + part) * kPartialFloats) + tid;
+#pragma unroll
+        for (int a = 0; a < FM; ++a)
+#pragma unroll
+            for (int b = 0; b < FN; ++b)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 t = src[(size_t)((a * FN + b) * 4 + g) * kThreads];
+                    acc[a][b][4 * g] += t[0]; acc[a][b][4 * g + 1] += t[1];
+                    acc[a][b][4 * g + 2] += t[2]; acc[a][b][4 * g + 3] += t[3];
+                }
     }
-    const long long tiles = (long long)mt_max * (npad / BN);
-    const long long grid = (tiles + 7) / 8 * 8;
-    if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
-    hipLaunchKernelGGL((ffn_bf16_kernel<BM, BN, UP>), dim3((unsigned)grid), dim3(256), smem, s, A, Wp, expert_stride, K, npad, C, ldc, plan);
-    return check_launch("moe_expert_ffn_grouped gemm launch");
+    epilogue<false>(acc, smem, C, ldc, w, wave, lane);
+}
+
+static int cus_per_xcd() {
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= kXcds)
+            cached = cus / kXcds < kMaxCusPerXcd ? cus / kXcds : kMaxCusPerXcd;
+        else
+            cached = 32;
+    }
+    return cached;
+}
+
+template <typename Kernel>
+static int set_smem(Kernel k, int bytes) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    return e == hipSuccess ? MOE_OK : hip_fail(e, "hipFuncSetAttribute");
 }
 
 int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
                     const int32_t* starts, const int32_t* placement, int local_gpu, void* out,
                     int32_t* plan, void* H, hipStream_t s) {
-    constexpr int BM = 128, BN = 128;
+    static bool configured = false;
+    static bool split_down = true;
+    if (!configured) {
+        int rc;
+        if ((rc = set_smem(&ffn_bf16_kernel<true, false>, smem_bytes<true>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_kernel<false, false>, smem_bytes<false>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_kernel<false, true>, smem_bytes<false>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_fixup_kernel, smem_bytes<false>())) != MOE_OK) return rc;
+        const char* v = getenv("MOE_FFN_SPLIT");
+        if (v) split_down = atoi(v) != 0;
+        configured = true;
+    }
     int rc = launch_ffn_plan(counts, starts, placement, local_gpu, E, N, BM, BM, plan, s);
     if (rc != MOE_OK) return rc;
-    const int mt_max = (N + BM - 1) / BM + (E < N ? E : N);
+    const int cpx = cus_per_xcd();
+    const long long mt_max = (N + BM - 1) / BM + (E < N ? E : N);     // sum of ceil(n_e / BM) never exceeds this
     const size_t s13 = npad13(f) * d, s2 = npad2(d) * f, stride = s13 + s2;
     const uint16_t* Wp = (const uint16_t*)packed;
+    // partial tiles live behind H in the workspace
+    float* partials = (float*)((char*)H + round_up((size_t)N * f * 2, 256));
+    auto grid_for = [&](size_t npad, bool split) {
+        const long long tiles = mt_max * (long long)(npad / BN);
+        return (long long)kXcds * ((tiles + kXcds - 1) / kXcds + (split ? cpx : 0));
+    };
     {
+        const long long grid = grid_for(npad13(f), false);
+        if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
         LaunchTimer timer(MOE_K_FFN_UP, s);
-        rc = launch_gemm<BM, BN, true>((const uint16_t*)a, Wp, stride, d, (int)npad13(f), (uint16_t*)H, f, plan, mt_max, s);
-        if (rc != MOE_OK) return rc;
+        hipLaunchKernelGGL((ffn_bf16_kernel<true, false>), dim3((unsigned)grid), dim3(kThreads), smem_bytes<true>(), s,
+                           (const uint16_t*)a, Wp, stride, d, (int)npad13(f), (uint16_t*)H, f, plan, partials, cpx);
+        if ((rc = check_launch("moe_expert_ffn_grouped up launch")) != MOE_OK) return rc;
     }
     {
+        const long long grid = grid_for(npad2(d), split_down);
+        if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
         LaunchTimer timer(MOE_K_FFN_DOWN, s);
-        rc = launch_gemm<BM, BN, false>((const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, mt_max, s);
-        if (rc != MOE_OK) return rc;
+        if (split_down) {
+            hipLaunchKernelGGL((ffn_bf16_kernel<false, true>), dim3((unsigned)grid), dim3(kThreads), smem_bytes<false>(), s,
+                               (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx);
+            if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
+            hipLaunchKernelGGL(ffn_bf16_fixup_kernel, dim3(kXcds * (cpx / 2)), dim3(kThreads), smem_bytes<false>(), s, f,
+                               (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx);
+            if ((rc = check_launch("moe_expert_ffn_grouped fix-up launch")) != MOE_OK) return rc;
+        } else {
+            hipLaunchKernelGGL((ffn_bf16_kernel<false, false>), dim3((unsigned)grid), dim3(kThreads), smem_bytes<false>(), s,
+                               (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx);
+            if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
+        }
     }
     return MOE_OK;
 }
