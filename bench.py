@@ -32,6 +32,11 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# Bytes that cross the L2 boundary per launch of the dominant kernel (up projection), from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain 1 GiB copy of known size; the summary
+# and the commands are in profiles/bench_c2_rocprofv3.md.  Only known for the default workload.
+MEASURED_TRAFFIC_BYTES = {"c2": 5027.4e6 + 234.9e6}
+
 
 def cpu_baseline(cfg, x, lg, weights, pl, budget_rows=8192):
     """The oracle as it stands, on the host: gate and dispatch over the whole
@@ -80,6 +85,9 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy three times, so that a rocprofv3 --pmc run of this "
+                         "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE with")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); run it with --gpus 1")
@@ -135,7 +143,7 @@ def main():
     achieved = up_flops / (up_ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else 157.3
     roofline = {"bound": "mfma", "kernel": "ffn_up (A.[W1|W3] + SwiGLU)", "achieved": round(achieved, 2), "peak": peak,
-                "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
                 "ms": round(up_ms, 4), "flops_per_launch": up_flops}
 
     out = {
@@ -147,6 +155,14 @@ def main():
                    "routes_on_this_gpu": n_local, "largest_expert_share": round(float(counts.max()) / max(1, counts.sum()), 4)},
         "roofline": roofline,
     }
+
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if not args.no_breakdown:
         n_rep = max(5, min(args.steps, 20))
