@@ -107,10 +107,10 @@ int moe_topk_gate(const float* logits, int T, int E, int k, int32_t* topk_idx, f
 
 size_t moe_dispatch_workspace_bytes(int T, int E, int k) {
     if (T < 0 || E < 1 || k < 1) return 0;
-    size_t N = (size_t)T * k;
-    size_t nb = (N + kDispatchChunk - 1) / kDispatchChunk;
+    int items = 0, nb = 0;
+    dispatch_geometry((long long)T * k, &items, &nb);
     if (nb == 0) nb = 1;
-    return round_up(nb * (size_t)E * sizeof(int32_t), 256);
+    return round_up((size_t)nb * (size_t)E * sizeof(int32_t), 256);
 }
 
 int moe_dispatch(const void* x, moe_dtype_t dt, const int32_t* topk_idx, int T, int d, int E, int k,

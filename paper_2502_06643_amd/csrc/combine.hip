@@ -62,6 +62,65 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
     y[u] = o;
 }
 
+// Wide rows: one workgroup per token.  The token's k routes (expert, sorted position, weight) are
+// wave-uniform, so they are read once with scalar loads, and every thread then has its k row
+// gathers in flight at the same time.
+template <bool BF16, int UNITS_PER_THREAD>
+__global__ __launch_bounds__(256) void combine_token_kernel(const uint4* __restrict__ ffn_out, const int32_t* __restrict__ inv_perm,
+                                                            const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
+                                                            const int32_t* __restrict__ placement, int local_gpu,
+                                                            int units_per_row, int E, int k, int N, uint4* __restrict__ y) {
+    const long long t = blockIdx.x;
+    float acc[UNITS_PER_THREAD][8];
+#pragma unroll
+    for (int i = 0; i < UNITS_PER_THREAD; ++i)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
+    for (int j = 0; j < k; ++j) {
+        const long long r = t * k + j;
+        if (local_gpu >= 0) {
+            const int e = topk_idx[r];
+            if ((unsigned)e >= (unsigned)E || placement[e] != local_gpu) continue;
+        }
+        const int p = inv_perm[r];
+        if ((unsigned)p >= (unsigned)N) continue;
+        const float w = topk_w[r];
+        const uint4* row = ffn_out + (long long)p * units_per_row;
+        uint4 v[UNITS_PER_THREAD];
+#pragma unroll
+        for (int i = 0; i < UNITS_PER_THREAD; ++i) {
+            const int c = threadIdx.x + i * 256;
+            v[i] = (c < units_per_row) ? row[c] : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int i = 0; i < UNITS_PER_THREAD; ++i) {
+            if (BF16) {
+                acc[i][0] = fmaf(w, bf16_lo(v[i].x), acc[i][0]); acc[i][1] = fmaf(w, bf16_hi(v[i].x), acc[i][1]);
+                acc[i][2] = fmaf(w, bf16_lo(v[i].y), acc[i][2]); acc[i][3] = fmaf(w, bf16_hi(v[i].y), acc[i][3]);
+                acc[i][4] = fmaf(w, bf16_lo(v[i].z), acc[i][4]); acc[i][5] = fmaf(w, bf16_hi(v[i].z), acc[i][5]);
+                acc[i][6] = fmaf(w, bf16_lo(v[i].w), acc[i][6]); acc[i][7] = fmaf(w, bf16_hi(v[i].w), acc[i][7]);
+            } else {
+                acc[i][0] = fmaf(w, __uint_as_float(v[i].x), acc[i][0]); acc[i][1] = fmaf(w, __uint_as_float(v[i].y), acc[i][1]);
+                acc[i][2] = fmaf(w, __uint_as_float(v[i].z), acc[i][2]); acc[i][3] = fmaf(w, __uint_as_float(v[i].w), acc[i][3]);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < UNITS_PER_THREAD; ++i) {
+        const int c = threadIdx.x + i * 256;
+        if (c >= units_per_row) break;
+        uint4 o;
+        if (BF16) {
+            o.x = pack_bf16(acc[i][0], acc[i][1]); o.y = pack_bf16(acc[i][2], acc[i][3]);
+            o.z = pack_bf16(acc[i][4], acc[i][5]); o.w = pack_bf16(acc[i][6], acc[i][7]);
+        } else {
+            o.x = __float_as_uint(acc[i][0]); o.y = __float_as_uint(acc[i][1]);
+            o.z = __float_as_uint(acc[i][2]); o.w = __float_as_uint(acc[i][3]);
+        }
+        y[t * units_per_row + c] = o;
+    }
+}
+
 int launch_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm, const int32_t* topk_idx,
                    const float* topk_w, const int32_t* placement, int local_gpu, int T, int d, int E, int k,
                    void* y, hipStream_t s) {
@@ -70,12 +129,24 @@ int launch_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm,
     const long long grid = (total_units + 255) / 256;
     if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_combine: T*d too large for one launch");
     LaunchTimer timer(MOE_K_COMBINE, s);
-    if (dt == MOE_BF16)
+    const bool bf = dt == MOE_BF16;
+#define MOE_LAUNCH_TOKEN(BF, UPT)                                                                                   \
+    hipLaunchKernelGGL((combine_token_kernel<BF, UPT>), dim3((unsigned)T), dim3(256), 0, s, (const uint4*)ffn_out, \
+                       inv_perm, topk_idx, topk_w, placement, local_gpu, units_per_row, E, k, T * k, (uint4*)y)
+    if (units_per_row >= 192 && units_per_row <= 256) {
+        if (bf) MOE_LAUNCH_TOKEN(true, 1); else MOE_LAUNCH_TOKEN(false, 1);
+    } else if (units_per_row > 256 && units_per_row <= 512) {
+        if (bf) MOE_LAUNCH_TOKEN(true, 2); else MOE_LAUNCH_TOKEN(false, 2);
+    } else if (units_per_row > 512 && units_per_row <= 1024) {
+        if (bf) MOE_LAUNCH_TOKEN(true, 4); else MOE_LAUNCH_TOKEN(false, 4);
+    } else if (bf) {
         hipLaunchKernelGGL(combine_kernel<true>, dim3((unsigned)grid), dim3(256), 0, s, (const uint4*)ffn_out, inv_perm, topk_idx,
                            topk_w, placement, local_gpu, total_units, units_per_row, E, k, T * k, (uint4*)y);
-    else
+    } else {
         hipLaunchKernelGGL(combine_kernel<false>, dim3((unsigned)grid), dim3(256), 0, s, (const uint4*)ffn_out, inv_perm, topk_idx,
                            topk_w, placement, local_gpu, total_units, units_per_row, E, k, T * k, (uint4*)y);
+    }
+#undef MOE_LAUNCH_TOKEN
     return check_launch("moe_combine launch");
 }
 

@@ -39,7 +39,7 @@ int launch_gate(const float* logits, int T, int E, int k, int32_t* idx, float* w
 
 constexpr int kDispatchBlock = 256;
 constexpr int kDispatchItems = 4;
-constexpr int kDispatchChunk = kDispatchBlock * kDispatchItems;   // routes per workgroup
+void dispatch_geometry(long long N, int* items, int* nblocks);      // routes per thread and number of chunks
 int launch_dispatch(const void* x, int row_bytes, const int32_t* topk_idx, int T, int E, int k,
                     const int32_t* placement, int G, void* send_buf, int32_t* perm, int32_t* inv_perm,
                     int32_t* expert_counts, int32_t* expert_start, int32_t* gpu_counts,

@@ -20,16 +20,25 @@
 namespace moe {
 
 constexpr int kWaves = kDispatchBlock / 64;
-constexpr int kRoutesPerWave = 64 * kDispatchItems;
+constexpr int kMaxChunks = 1024;     // the scan walks this many per-chunk histograms at most
 
-__global__ __launch_bounds__(kDispatchBlock) void dispatch_count_kernel(const int32_t* __restrict__ topk_idx, int N, int E,
+// Routes per thread: 4 for ordinary batches, more for very large ones so that the number of chunks
+// (and with it the scan) stays bounded.
+void dispatch_geometry(long long N, int* items, int* nblocks) {
+    long long it = (N + (long long)kMaxChunks * kDispatchBlock - 1) / ((long long)kMaxChunks * kDispatchBlock);
+    if (it < kDispatchItems) it = kDispatchItems;
+    it = (it + 3) / 4 * 4;
+    *items = (int)it;
+    *nblocks = (int)((N + it * kDispatchBlock - 1) / (it * kDispatchBlock));
+}
+
+__global__ __launch_bounds__(kDispatchBlock) void dispatch_count_kernel(const int32_t* __restrict__ topk_idx, int N, int E, int items,
                                                                         int32_t* __restrict__ block_counts) {
     __shared__ int hist[MOE_MAX_EXPERTS];
     for (int e = threadIdx.x; e < E; e += kDispatchBlock) hist[e] = 0;
     __syncthreads();
-    const long long base = (long long)blockIdx.x * kDispatchChunk;
-#pragma unroll
-    for (int i = 0; i < kDispatchItems; ++i) {
+    const long long base = (long long)blockIdx.x * kDispatchBlock * items;
+    for (int i = 0; i < items; ++i) {
         const long long r = base + i * kDispatchBlock + threadIdx.x;
         if (r < N) {
             const int e = topk_idx[r];
@@ -40,37 +49,53 @@ __global__ __launch_bounds__(kDispatchBlock) void dispatch_count_kernel(const in
     for (int e = threadIdx.x; e < E; e += kDispatchBlock) block_counts[(size_t)blockIdx.x * E + e] = hist[e];
 }
 
-__global__ __launch_bounds__(256) void dispatch_scan_kernel(int32_t* __restrict__ block_counts, int nblocks, int E,
+constexpr int kScanThreads = 1024;
+
+__global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(int32_t* __restrict__ block_counts, int nblocks, int E, int EP,
                                                             const int32_t* __restrict__ placement, int G,
                                                             int32_t* __restrict__ expert_counts,
                                                             int32_t* __restrict__ expert_start,
                                                             int32_t* __restrict__ gpu_counts,
                                                             int32_t* __restrict__ gpu_offsets) {
+    // EP = E rounded up to a power of two; the threads form kScanThreads/EP slices of the chunk range,
+    // each thread owning one expert in one slice
     __shared__ int pl[MOE_MAX_EXPERTS];
     __shared__ int tot[MOE_MAX_EXPERTS];
-    const int e = threadIdx.x;
+    __shared__ int slice_tot[kScanThreads];
+    const int e = threadIdx.x % EP, sl = threadIdx.x / EP, S = kScanThreads / EP;
+    const int per = (nblocks + S - 1) / S;
+    const int b0 = sl * per, b1 = min(nblocks, b0 + per);
+    int sum = 0;
+    if (e < E)
+        for (int b = b0; b < b1; ++b) sum += block_counts[(size_t)b * E + e];
+    slice_tot[threadIdx.x] = sum;
+    if (threadIdx.x < E) pl[threadIdx.x] = placement[threadIdx.x];
+    __syncthreads();
     if (e < E) {
-        pl[e] = placement[e];
         int run = 0;
-        for (int b = 0; b < nblocks; ++b) {
+        for (int s2 = 0; s2 < sl; ++s2) run += slice_tot[s2 * EP + e];
+        if (sl == S - 1) {
+            tot[e] = run + sum;
+            expert_counts[e] = run + sum;
+        }
+        for (int b = b0; b < b1; ++b) {
             const int c = block_counts[(size_t)b * E + e];
             block_counts[(size_t)b * E + e] = run;      // exclusive prefix over chunks, per expert
             run += c;
         }
-        tot[e] = run;
-        expert_counts[e] = run;
     }
     __syncthreads();
-    if (e < E) {
+    if (threadIdx.x < E) {
+        const int me = threadIdx.x;
         int start = 0;
-        const int ge = pl[e];
+        const int ge = pl[me];
         for (int o = 0; o < E; ++o) {
             const int go = pl[o];
-            if (go < ge || (go == ge && o < e)) start += tot[o];
+            if (go < ge || (go == ge && o < me)) start += tot[o];
         }
-        expert_start[e] = start;
+        expert_start[me] = start;
     }
-    for (int g = threadIdx.x; g < G; g += 256) {
+    for (int g = threadIdx.x; g < G; g += kScanThreads) {
         int cnt = 0, off = 0;
         for (int o = 0; o < E; ++o) {
             const int go = pl[o];
@@ -94,7 +119,7 @@ __device__ __forceinline__ unsigned long long match_expert(int e, bool valid, in
     return m;
 }
 
-__global__ __launch_bounds__(kDispatchBlock) void dispatch_rank_kernel(const int32_t* __restrict__ topk_idx, int N, int E, int ebits,
+__global__ __launch_bounds__(kDispatchBlock) void dispatch_rank_kernel(const int32_t* __restrict__ topk_idx, int N, int E, int ebits, int items,
                                                                        const int32_t* __restrict__ block_counts,
                                                                        const int32_t* __restrict__ expert_start,
                                                                        int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
@@ -105,17 +130,14 @@ __global__ __launch_bounds__(kDispatchBlock) void dispatch_rank_kernel(const int
     for (int i = threadIdx.x; i < kWaves * MOE_MAX_EXPERTS; i += kDispatchBlock) (&woff[0][0])[i] = 0;
     __syncthreads();
 
-    const long long wbase = (long long)blockIdx.x * kDispatchChunk + (long long)wave * kRoutesPerWave;
-    int ex[kDispatchItems];
-    bool ok[kDispatchItems];
+    const long long wbase = ((long long)blockIdx.x * kWaves + wave) * 64 * items;
     const unsigned long long lower = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int i = 0; i < kDispatchItems; ++i) {
+    for (int i = 0; i < items; ++i) {
         const long long r = wbase + i * 64 + lane;
-        ex[i] = (r < N) ? topk_idx[r] : -1;
-        ok[i] = (unsigned)ex[i] < (unsigned)E;
-        const unsigned long long m = match_expert(ex[i], ok[i], ebits);
-        if (ok[i] && (m & lower) == 0ull) atomicAdd(&woff[wave][ex[i]], __popcll(m));   // first lane of the group
+        const int ex = (r < N) ? topk_idx[r] : -1;
+        const bool ok = (unsigned)ex < (unsigned)E;
+        const unsigned long long m = match_expert(ex, ok, ebits);
+        if (ok && (m & lower) == 0ull) atomicAdd(&woff[wave][ex], __popcll(m));   // first lane of the group
     }
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += kDispatchBlock) {
@@ -129,16 +151,17 @@ __global__ __launch_bounds__(kDispatchBlock) void dispatch_rank_kernel(const int
     }
     __syncthreads();
     volatile int* my = woff[wave];
-#pragma unroll
-    for (int i = 0; i < kDispatchItems; ++i) {
+    for (int i = 0; i < items; ++i) {
         const long long r = wbase + i * 64 + lane;
-        const unsigned long long m = match_expert(ex[i], ok[i], ebits);
+        const int ex = (r < N) ? topk_idx[r] : -1;
+        const bool ok = (unsigned)ex < (unsigned)E;
+        const unsigned long long m = match_expert(ex, ok, ebits);
         int pos = 0;
-        if (ok[i]) pos = my[ex[i]] + __popcll(m & lower);
+        if (ok) pos = my[ex] + __popcll(m & lower);
         __builtin_amdgcn_wave_barrier();
-        if (ok[i] && (m & lower) == 0ull) my[ex[i]] += __popcll(m);
+        if (ok && (m & lower) == 0ull) my[ex] += __popcll(m);
         __builtin_amdgcn_wave_barrier();
-        if (ok[i]) {
+        if (ok) {
             perm[pos] = (int32_t)r;
             inv_perm[r] = pos;
         }
@@ -165,24 +188,26 @@ int launch_dispatch(const void* x, int row_bytes, const int32_t* topk_idx, int T
                     int32_t* expert_counts, int32_t* expert_start, int32_t* gpu_counts,
                     int32_t* gpu_offsets, int32_t* block_counts, hipStream_t s) {
     const int N = T * k;
-    const int nblocks = (N + kDispatchChunk - 1) / kDispatchChunk;
+    int items, nblocks;
+    dispatch_geometry(N, &items, &nblocks);
     int ebits = 0;
     while ((1 << ebits) < E) ++ebits;
+    const int EP = 1 << ebits;
     int rc;
     if (nblocks > 0) {
         LaunchTimer timer(MOE_K_DISPATCH_COUNT, s);
-        hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, block_counts);
+        hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, items, block_counts);
         if ((rc = check_launch("moe_dispatch count launch")) != MOE_OK) return rc;
     }
     {
         LaunchTimer timer(MOE_K_DISPATCH_SCAN, s);
-        hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(256), 0, s, block_counts, nblocks, E, placement, G,
+        hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, block_counts, nblocks, E, EP, placement, G,
                            expert_counts, expert_start, gpu_counts, gpu_offsets);
         if ((rc = check_launch("moe_dispatch scan launch")) != MOE_OK) return rc;
     }
     if (nblocks > 0) {
         LaunchTimer timer(MOE_K_DISPATCH_RANK, s);
-        hipLaunchKernelGGL(dispatch_rank_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, ebits,
+        hipLaunchKernelGGL(dispatch_rank_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, ebits, items,
                            block_counts, expert_start, perm, inv_perm);
         if ((rc = check_launch("moe_dispatch rank launch")) != MOE_OK) return rc;
     }

@@ -1,104 +1,126 @@
 // moe_topk_gate: top-k router (paper Section 2.1).
 //
-// A token's E logits are spread over L neighbouring lanes of a wavefront, four
-// consecutive logits per lane (one 16-byte load when E % 4 == 0), so a
-// wavefront reads 64/L whole rows as one contiguous block.  Each logit becomes
-// a 64-bit key  (order-preserving bits of the float) << 32 | ~expert , for
-// which "larger key" is exactly "larger logit, ties to the lower expert".  k
-// rounds of (best of my four) -> (xor-butterfly max over the L lanes) select
-// the experts in descending order; the winner's key is retired by its owner.
-// Weights are the softmax over the k selected logits in fp32.
+// A token's E logits are spread over L neighbouring lanes of a wavefront, VPL
+// consecutive logits per lane (16-byte loads when E % 4 == 0), so a wavefront
+// reads 64/L whole rows.  Each logit is mapped to an order-preserving unsigned
+// key (-0.0 is folded onto +0.0 first, so the two tie); key 0 is below every
+// finite logit and marks "no candidate".  One round = scan my VPL keys with a
+// strict '>' (ascending index, so the lowest index wins a tie), then an
+// xor-butterfly over the L lanes on (key, index) with the same tie rule, then
+// the owner retires the winner.  k rounds give the experts in descending logit
+// order.  Weights are the softmax over the k selected logits in fp32.
 #include "common.h"
 
 namespace moe {
 
 __device__ __forceinline__ uint32_t orderable(float v) {
     if (v == 0.0f) v = 0.0f;                       // -0.0 and +0.0 tie
-    uint32_t u = __float_as_uint(v);
+    const uint32_t u = __float_as_uint(v);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
 __device__ __forceinline__ float from_orderable(uint32_t o) {
-    uint32_t u = (o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o;
+    const uint32_t u = (o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o;
     return __uint_as_float(u);
 }
 
-__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int m) {
-    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-    lo = __shfl_xor(lo, m, 64);
-    hi = __shfl_xor(hi, m, 64);
-    return ((unsigned long long)hi << 32) | lo;
-}
-
-template <int L>
+template <int L, int VPL, int KMAX>
 __global__ __launch_bounds__(256) void gate_kernel(const float* __restrict__ logits, int T, int E, int k,
                                                    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
     constexpr int TOK_PER_BLOCK = 256 / L;
     const int sub = threadIdx.x % L;
     const long long t = (long long)blockIdx.x * TOK_PER_BLOCK + threadIdx.x / L;
     const bool live = t < T;
-    const int e0 = sub * 4;
+    const int e0 = sub * VPL;
 
-    unsigned long long key[4] = {0ull, 0ull, 0ull, 0ull};      // 0 = "no candidate"
-    if (live && e0 < E) {
+    uint32_t key[VPL];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) key[i] = 0u;
+    if (live) {
         const float* row = logits + t * E;
-        float v[4];
         if ((E & 3) == 0) {
-            const float4 q = *reinterpret_cast<const float4*>(row + e0);
-            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+#pragma unroll
+            for (int c = 0; c < VPL / 4; ++c) {
+                if (e0 + 4 * c < E) {
+                    const float4 q = *reinterpret_cast<const float4*>(row + e0 + 4 * c);
+                    key[4 * c] = orderable(q.x); key[4 * c + 1] = orderable(q.y);
+                    key[4 * c + 2] = orderable(q.z); key[4 * c + 3] = orderable(q.w);
+                }
+            }
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = (e0 + i < E) ? row[e0 + i] : 0.f;
+            for (int i = 0; i < VPL; ++i)
+                if (e0 + i < E) key[i] = orderable(row[e0 + i]);
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (e0 + i < E)
-                key[i] = ((unsigned long long)orderable(v[i]) << 32) | (uint32_t)(~(uint32_t)(e0 + i));
     }
 
+    // KMAX >= k is a compile-time bound so that the selected experts and weights stay in registers
+    // and are written once
     float top = 0.f, denom = 0.f;
-    for (int j = 0; j < k; ++j) {
-        unsigned long long best = key[0];
+    float p_sel[KMAX];
+    int e_sel[KMAX];
 #pragma unroll
-        for (int i = 1; i < 4; ++i) best = key[i] > best ? key[i] : best;
+    for (int j = 0; j < KMAX; ++j) {
+        p_sel[j] = 0.f;
+        e_sel[j] = 0;
+        if (j < k) {
+            uint32_t best = key[0];
+            int bi = 0;
 #pragma unroll
-        for (int m = 1; m < L; m <<= 1) {
-            const unsigned long long o = shfl_xor_u64(best, m);
-            best = o > best ? o : best;
-        }
-        const uint32_t e_win = ~(uint32_t)best;
+            for (int i = 1; i < VPL; ++i)
+                if (key[i] > best) { best = key[i]; bi = i; }
+            int be = e0 + bi;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if ((uint32_t)(e0 + i) == e_win) key[i] = 0ull;
-        const float lj = from_orderable((uint32_t)(best >> 32));
-        if (j == 0) top = lj;
-        const float p = expf(lj - top);              // exp(0) = 1 for the top-1 expert
-        denom += p;
-        if (live && sub == 0) {
-            topk_idx[t * k + j] = (int32_t)e_win;
-            topk_w[t * k + j] = p;                   // normalised below by the same lane
+            for (int m = 1; m < L; m <<= 1) {
+                const uint32_t ok = __shfl_xor(best, m, 64);
+                const int oe = __shfl_xor(be, m, 64);
+                if (ok > best || (ok == best && oe < be)) { best = ok; be = oe; }
+            }
+            const int mine = be - e0;               // in [0,VPL) only for the owner lane
+#pragma unroll
+            for (int i = 0; i < VPL; ++i)
+                if (i == mine) key[i] = 0u;
+            const float lj = from_orderable(best);
+            if (j == 0) top = lj;
+            const float p = expf(lj - top);         // exp(0) = 1 for the top-1 expert
+            denom += p;
+            p_sel[j] = p;
+            e_sel[j] = be;
         }
     }
-    if (live && sub == 0)
-        for (int j = 0; j < k; ++j) topk_w[t * k + j] = topk_w[t * k + j] / denom;
+    if (live && sub == 0) {
+        if (KMAX == 2 && k == 2) {                  // the common top-2 case: one 8-byte store each
+            *reinterpret_cast<int2*>(topk_idx + t * 2) = make_int2(e_sel[0], e_sel[1]);
+            *reinterpret_cast<float2*>(topk_w + t * 2) = make_float2(p_sel[0] / denom, p_sel[1] / denom);
+        } else {
+#pragma unroll
+            for (int j = 0; j < KMAX; ++j)
+                if (j < k) {
+                    topk_idx[t * k + j] = e_sel[j];
+                    topk_w[t * k + j] = p_sel[j] / denom;
+                }
+        }
+    }
 }
 
-template <int L>
+template <int L, int VPL>
 static void launch_l(const float* logits, int T, int E, int k, int32_t* idx, float* w, hipStream_t s) {
     constexpr int TOK_PER_BLOCK = 256 / L;
     const unsigned grid = (unsigned)(((long long)T + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK);
-    hipLaunchKernelGGL(gate_kernel<L>, dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
+    if (k <= 2) hipLaunchKernelGGL((gate_kernel<L, VPL, 2>), dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
+    else if (k <= 8) hipLaunchKernelGGL((gate_kernel<L, VPL, 8>), dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
+    else hipLaunchKernelGGL((gate_kernel<L, VPL, MOE_MAX_TOPK>), dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
 }
 
 int launch_gate(const float* logits, int T, int E, int k, int32_t* idx, float* w, hipStream_t s) {
     LaunchTimer timer(MOE_K_GATE, s);
-    const int lanes = (E + 3) / 4;
-    if (lanes <= 2) launch_l<2>(logits, T, E, k, idx, w, s);
-    else if (lanes <= 4) launch_l<4>(logits, T, E, k, idx, w, s);
-    else if (lanes <= 8) launch_l<8>(logits, T, E, k, idx, w, s);
-    else if (lanes <= 16) launch_l<16>(logits, T, E, k, idx, w, s);
-    else if (lanes <= 32) launch_l<32>(logits, T, E, k, idx, w, s);
-    else launch_l<64>(logits, T, E, k, idx, w, s);
+    if (E <= 4) launch_l<1, 4>(logits, T, E, k, idx, w, s);
+    else if (E <= 8) launch_l<1, 8>(logits, T, E, k, idx, w, s);
+    else if (E <= 16) launch_l<2, 8>(logits, T, E, k, idx, w, s);
+    else if (E <= 32) launch_l<4, 8>(logits, T, E, k, idx, w, s);
+    else if (E <= 64) launch_l<4, 16>(logits, T, E, k, idx, w, s);
+    else if (E <= 128) launch_l<8, 16>(logits, T, E, k, idx, w, s);
+    else launch_l<16, 16>(logits, T, E, k, idx, w, s);
     return check_launch("moe_topk_gate launch");
 }
 

@@ -2,11 +2,13 @@
 // R_{e1,e2,l} of the paper (Section 2.4; Section 3.1 "Token Routing Profile";
 // ILP 2 inputs).
 //
-// Each workgroup keeps a private int32 copy of the E_l x E_l1 table in LDS,
-// counts its tokens' k_l * k_l1 expert pairs there with LDS atomics, and then
-// adds its non-zero bins to the int64 table in memory.  Integer adds commute,
-// so the result is exact whatever the order.  Tables too large for LDS are
-// counted straight into memory.
+// Each workgroup keeps private int32 copies of the E_l x E_l1 table in LDS
+// (as many copies as fit, up to 32, selected by lane so that lanes hitting the
+// same hot bin mostly land on different addresses), counts its tokens'
+// k_l * k_l1 expert pairs there with LDS atomics, and then adds its non-zero
+// bins to the int64 table in memory.  Integer adds commute, so the result is
+// exact whatever the order.  Tables too large for LDS are counted straight
+// into memory.
 #include "common.h"
 
 namespace moe {
@@ -16,25 +18,24 @@ constexpr int kTokPerThread = 4;
 
 template <bool USE_LDS>
 __global__ __launch_bounds__(256) void transition_kernel(const int32_t* __restrict__ idx_l, const int32_t* __restrict__ idx_l1,
-                                                         int T, int k_l, int k_l1, int E_l, int E_l1,
+                                                         int T, int k_l, int k_l1, int E_l, int E_l1, int copies,
                                                          unsigned long long* __restrict__ R) {
     extern __shared__ int hist[];
     const int bins = E_l * E_l1;
+    const int my_copy = threadIdx.x & (copies - 1);
     if (USE_LDS) {
-        for (int b = threadIdx.x; b < bins; b += 256) hist[b] = 0;
+        for (int b = threadIdx.x; b < bins * copies; b += 256) hist[b] = 0;
         __syncthreads();
     }
     const long long stride = (long long)gridDim.x * 256;
     for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < T; t += stride) {
-        int b1[MOE_MAX_TOPK];
-        for (int j2 = 0; j2 < k_l1; ++j2) b1[j2] = idx_l1[t * k_l1 + j2];
         for (int j1 = 0; j1 < k_l; ++j1) {
             const int e1 = idx_l[t * k_l + j1];
             if ((unsigned)e1 >= (unsigned)E_l) continue;
             for (int j2 = 0; j2 < k_l1; ++j2) {
-                const int e2 = b1[j2];
+                const int e2 = idx_l1[t * k_l1 + j2];        // re-read per pair: it stays in L1, and no private array is needed
                 if ((unsigned)e2 >= (unsigned)E_l1) continue;
-                if (USE_LDS) atomicAdd(&hist[e1 * E_l1 + e2], 1);
+                if (USE_LDS) atomicAdd(&hist[(e1 * E_l1 + e2) * copies + my_copy], 1);
                 else atomicAdd(&R[e1 * E_l1 + e2], 1ull);
             }
         }
@@ -42,7 +43,8 @@ __global__ __launch_bounds__(256) void transition_kernel(const int32_t* __restri
     if (USE_LDS) {
         __syncthreads();
         for (int b = threadIdx.x; b < bins; b += 256) {
-            const int c = hist[b];
+            int c = 0;
+            for (int i = 0; i < copies; ++i) c += hist[b * copies + ((i + threadIdx.x) & (copies - 1))];
             if (c) atomicAdd(&R[b], (unsigned long long)c);
         }
     }
@@ -52,13 +54,15 @@ int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_
                       int64_t* R, hipStream_t s) {
     const int bins = E_l * E_l1;
     long long want = ((long long)T + 256 * kTokPerThread - 1) / (256 * kTokPerThread);
-    const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 1024 ? 1024 : want));
+    const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 512 ? 512 : want));
+    int copies = 1;
+    while (copies < 32 && bins * copies * 2 <= kLdsBins) copies *= 2;
     LaunchTimer timer(MOE_K_TRANSITION, s);
     if (bins <= kLdsBins)
-        hipLaunchKernelGGL(transition_kernel<true>, dim3(grid), dim3(256), bins * sizeof(int), s, idx_l, idx_l1, T, k_l, k_l1,
-                           E_l, E_l1, (unsigned long long*)R);
+        hipLaunchKernelGGL(transition_kernel<true>, dim3(grid), dim3(256), bins * copies * sizeof(int), s, idx_l, idx_l1, T, k_l, k_l1,
+                           E_l, E_l1, copies, (unsigned long long*)R);
     else
-        hipLaunchKernelGGL(transition_kernel<false>, dim3(grid), dim3(256), 0, s, idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1,
+        hipLaunchKernelGGL(transition_kernel<false>, dim3(grid), dim3(256), 0, s, idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1, 1,
                            (unsigned long long*)R);
     return check_launch("moe_transition_counts launch");
 }
