@@ -5,8 +5,9 @@
 //   down: out = H W2_e                    [rows, d]  bf16, fp32 accumulate
 //
 // Work decomposition.  A workgroup of 8 wavefronts (4 along rows x 2 along
-// columns, 64 x 128 outputs each, two wavefronts per SIMD) owns one 256 x 256
-// output tile of one expert; the (expert, row tile) list comes from the
+// columns, two wavefronts per SIMD) owns one 256 x 256 output tile of one
+// expert (64 x 128 per wavefront), or 384 x 256 (96 x 128 per wavefront) when
+// buckets are large on average; the (expert, row tile) list comes from the
 // device-side plan, so no bucket size ever reaches the host.  Workgroup ids are
 // dealt round-robin to the 8 XCDs by the hardware; tile ids are assigned so
 // that every XCD works on a contiguous range ordered expert -> column tile ->
@@ -47,7 +48,6 @@
 // transposed through a per-wavefront LDS staging tile and written with
 // 16-byte stores that cover whole 128-byte lines.
 #include "ffn_plan.h"
-#include <cstdlib>
 
 namespace moe {
 
@@ -56,23 +56,27 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int BM = 256, BN = 256, BK = 64;      // workgroup tile and k depth of one LDS stage
+// The workgroup tile is (128 * FM) x 256 with FM = 2 or 3 fragment rows per wavefront (template parameter).
+constexpr int BN = 256, BK = 64;                // tile width and k depth of one LDS stage
 constexpr int WM = 4, WN = 2, NW = WM * WN;     // wavefront grid
-constexpr int WTM = BM / WM, WTN = BN / WN;     // 64 x 128 per wavefront
-constexpr int FM = WTM / 32, FN = WTN / 32;     // 2 x 4 fragments of 32 x 32
+constexpr int WTN = BN / WN;                    // 128 columns per wavefront
+constexpr int FN = WTN / 32;                    // 4 column fragments of 32
 constexpr int NS = 2;                           // LDS stages
 constexpr int KB = BK / 16;                     // k-blocks per stage
-constexpr int STAGE = (BM + BN) * BK;           // elements per stage
-constexpr int A_CHUNKS = BM / 8, B_CHUNKS = BN / 8;             // 1 KB pieces per stage
-constexpr int A_PER_WAVE = A_CHUNKS / NW, B_PER_WAVE = B_CHUNKS / NW;
-constexpr int LPT = A_PER_WAVE + B_PER_WAVE;    // loads per wavefront and k tile
+constexpr int B_CHUNKS = BN / 8;                // 1 KB pieces of the weight tile per stage
+constexpr int B_PER_WAVE = B_CHUNKS / NW;
 constexpr int kThreads = NW * 64;
+template <int FM> struct Tile {
+    static constexpr int WTM = 32 * FM, BM = WM * WTM;
+    static constexpr int STAGE = (BM + BN) * BK;            // elements per stage
+    static constexpr int A_CHUNKS = BM / 8, A_PER_WAVE = A_CHUNKS / NW;
+    static constexpr size_t kPartialFloats = (size_t)BM * BN;
+};
 constexpr int kPanelCols = 32;
 constexpr int kXcds = 8;
 constexpr int kMaxSplit = 8;
 constexpr int kMinSplitKT = 16;                 // a k part is at least this many k tiles
-constexpr int kAccPerLane = FM * FN * 16;
-constexpr size_t kPartialFloats = (size_t)BM * BN;              // one fp32 partial tile
+constexpr size_t kMaxPartialFloats = (size_t)384 * BN;          // one fp32 partial tile of the largest tile
 
 static inline size_t npad13(int f) { return round_up((size_t)2 * f, BN); }
 static inline size_t npad2(int d) { return round_up((size_t)d, BN); }
@@ -83,7 +87,7 @@ size_t packed_bytes_bf16(int E, int d, int f) {
 
 // fp32 partial tiles for the split tail of the down projection: one slot per compute unit
 constexpr int kMaxCusPerXcd = 48;
-size_t ffn_bf16_scratch_bytes() { return (size_t)kXcds * kMaxCusPerXcd * kPartialFloats * sizeof(float); }
+size_t ffn_bf16_scratch_bytes() { return (size_t)kXcds * kMaxCusPerXcd * kMaxPartialFloats * sizeof(float); }
 
 // One thread per 16-byte unit of the packed buffer.  Unit index within one matrix of one expert:
 // (((nt * KT + kt) * 8 + panel) * 4 + kb) * 64 + lane.
@@ -178,7 +182,7 @@ __device__ __forceinline__ XcdShare xcd_share(long long total_tiles, int x, int 
 }
 
 __device__ __forceinline__ void locate_tile(const int32_t* __restrict__ plan, const int32_t* __restrict__ prefix, int NT,
-                                            long long tile, WorkItem& w) {
+                                            long long tile, int BM, WorkItem& w) {
     const int n_exp = plan[0];
     int i = 0;
     while (i + 1 < n_exp && (long long)prefix[i + 1] * NT <= tile) ++i;
@@ -202,9 +206,12 @@ __device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
 // acc += A[row0 .. row0+rows, k tiles kt0..kt1) * B(tile), everything through LDS
+template <int FM>
 __device__ __forceinline__ void mainloop(f32x16 (&acc)[FM][FN], uint16_t* smem, const uint16_t* __restrict__ A,
                                          const uint16_t* __restrict__ Bbase, int K, const WorkItem& w, int wave, int lane,
                                          bool wave_active) {
+    constexpr int WTM = Tile<FM>::WTM, BM = Tile<FM>::BM, STAGE = Tile<FM>::STAGE;
+    constexpr int A_CHUNKS = Tile<FM>::A_CHUNKS, A_PER_WAVE = Tile<FM>::A_PER_WAVE;
     const int wave_m = wave / WN, wave_n = wave % WN;
     const uint16_t* Abase = A + (size_t)w.row0 * K;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
@@ -262,22 +269,24 @@ __device__ __forceinline__ void mainloop(f32x16 (&acc)[FM][FN], uint16_t* smem, 
     }
 }
 
-// accumulators -> bf16 -> per-wavefront LDS staging tile -> 16-byte stores of whole lines.
-// accumulator v of a 32x32 fragment: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
-template <bool UP>
+// accumulators -> bf16 -> per-wavefront LDS staging tile (32 rows at a time) -> 16-byte stores of
+// whole lines.  accumulator v of a 32x32 fragment: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+template <bool UP, int FM>
 __device__ __forceinline__ void epilogue(const f32x16 (&acc)[FM][FN], uint16_t* smem, uint16_t* __restrict__ C, int ldc,
                                          const WorkItem& w, int wave, int lane) {
+    constexpr int WTM = Tile<FM>::WTM;
     constexpr int OUTC = UP ? WTN / 2 : WTN;          // output columns of this wavefront
     constexpr int RS = OUTC + 8;                      // staging row stride (elements); the pad staggers the banks
     constexpr int CPR = OUTC / 8;                     // 16-byte chunks per row
     constexpr int RPI = 64 / CPR;                     // rows covered by one wavefront-wide 16-byte access
     const int wave_m = wave / WN, wave_n = wave % WN;
-    uint16_t* stg = smem + wave * (WTM * RS);
+    uint16_t* stg = smem + wave * (32 * RS);
+    const int col = (UP ? w.nt * (BN / 2) : w.nt * BN) + wave_n * OUTC + (lane % CPR) * 8;
 #pragma unroll
     for (int a = 0; a < FM; ++a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int r = a * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
             if (UP) {
 #pragma unroll
                 for (int b = 0; b < FN; b += 2) {
@@ -291,31 +300,31 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[FM][FN], uint16_t* 
                     stg[r * RS + b * 32 + (lane & 31)] = __builtin_bit_cast(uint16_t, (__bf16)acc[a][b][v]);
             }
         }
-    }
-    const int col = (UP ? w.nt * (BN / 2) : w.nt * BN) + wave_n * OUTC + (lane % CPR) * 8;
 #pragma unroll
-    for (int it = 0; it < WTM / RPI; ++it) {
-        const int r = it * RPI + lane / CPR;
-        const int gr = wave_m * WTM + r;
-        if (gr < w.rows && col < ldc)
-            *reinterpret_cast<u32x4*>(C + (size_t)(w.row0 + gr) * ldc + col) =
-                *reinterpret_cast<const u32x4*>(stg + r * RS + (lane % CPR) * 8);
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int r = it * RPI + lane / CPR;
+            const int gr = wave_m * WTM + a * 32 + r;
+            if (gr < w.rows && col < ldc)
+                *reinterpret_cast<u32x4*>(C + (size_t)(w.row0 + gr) * ldc + col) =
+                    *reinterpret_cast<const u32x4*>(stg + r * RS + (lane % CPR) * 8);
+        }
     }
 }
 
-template <bool UP>
+template <bool UP, int FM>
 constexpr int smem_bytes() {
-    constexpr int stage_bytes = NS * STAGE * 2;
+    constexpr int stage_bytes = NS * Tile<FM>::STAGE * 2;
     constexpr int outc = UP ? WTN / 2 : WTN;
-    constexpr int epi_bytes = NW * WTM * (outc + 8) * 2;
+    constexpr int epi_bytes = NW * 32 * (outc + 8) * 2;
     return stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
 }
 
-template <bool UP, bool SPLIT>
+template <bool UP, bool SPLIT, int FM>
 __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ Wp,
                                                             size_t expert_stride, int K, int npad, uint16_t* __restrict__ C,
                                                             int ldc, const int32_t* __restrict__ plan, float* __restrict__ partials,
                                                             int cus_per_xcd) {
+    constexpr int WTM = Tile<FM>::WTM, BM = Tile<FM>::BM;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int32_t* prefix = plan + (UP ? kPlanTiles0 : kPlanTiles1);
     const int NT = npad / BN, KT = K / BK;
@@ -325,12 +334,12 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
     if (slot >= sh.full + sh.tail * sh.split) return;
     WorkItem w;
     if (slot < sh.full) {
-        locate_tile(plan, prefix, NT, sh.t_begin + slot, w);
+        locate_tile(plan, prefix, NT, sh.t_begin + slot, BM, w);
         w.kt0 = 0; w.kt1 = KT; w.partial = -1;
     } else {
         const int j = slot - sh.full;
         const int part = j % sh.split;
-        locate_tile(plan, prefix, NT, sh.t_begin + sh.full + j / sh.split, w);
+        locate_tile(plan, prefix, NT, sh.t_begin + sh.full + j / sh.split, BM, w);
         w.kt0 = (int)((long long)part * KT / sh.split);
         w.kt1 = (int)((long long)(part + 1) * KT / sh.split);
         w.partial = x * cus_per_xcd + j;
@@ -349,12 +358,12 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    mainloop(acc, smem, A, Bbase, K, w, wave, lane, wave_active);
+    mainloop<FM>(acc, smem, A, Bbase, K, w, wave, lane, wave_active);
 
     if (SPLIT && w.partial >= 0) {
         if (wave_active) {
             // 16 bytes per lane and store: [fragment][quad of accumulators][thread]
-            f32x4* dst = reinterpret_cast<f32x4*>(partials + (size_t)w.partial * kPartialFloats) + tid;
+            f32x4* dst = reinterpret_cast<f32x4*>(partials + (size_t)w.partial * Tile<FM>::kPartialFloats) + tid;
 #pragma unroll
             for (int a = 0; a < FM; ++a)
 #pragma unroll
@@ -368,13 +377,15 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
         return;
     }
     __syncthreads();                                  // the last tile's fragments have been read by everyone
-    if (wave_active) epilogue<UP>(acc, smem, C, ldc, w, wave, lane);
+    if (wave_active) epilogue<UP, FM>(acc, smem, C, ldc, w, wave, lane);
 }
 
 // adds the k parts of the split tail tiles in part order and writes the tiles
+template <int FM>
 __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npad, uint16_t* __restrict__ C, int ldc,
                                                                   const int32_t* __restrict__ plan,
                                                                   const float* __restrict__ partials, int cus_per_xcd) {
+    constexpr int WTM = Tile<FM>::WTM, BM = Tile<FM>::BM;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int32_t* prefix = plan + kPlanTiles1;
     const int NT = npad / BN, KT = K / BK;
@@ -383,7 +394,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
     const XcdShare sh = xcd_share(total, x, KT, cus_per_xcd, true);
     if (q >= sh.tail) return;
     WorkItem w;
-    locate_tile(plan, prefix, NT, sh.t_begin + sh.full + q, w);
+    locate_tile(plan, prefix, NT, sh.t_begin + sh.full + q, BM, w);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if ((wave / WN) * WTM >= w.rows) return;
@@ -395,7 +406,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
     for (int part = 0; part < sh.split; ++part) {
-        const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * cus_per_xcd + q * sh.split + part) * kPartialFloats) + tid;
+        const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * cus_per_xcd + q * sh.split + part) * Tile<FM>::kPartialFloats) + tid;
 #pragma unroll
         for (int a = 0; a < FM; ++a)
 #pragma unroll
@@ -407,7 +418,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
                     acc[a][b][4 * g + 2] += t[2]; acc[a][b][4 * g + 3] += t[3];
                 }
     }
-    epilogue<false>(acc, smem, C, ldc, w, wave, lane);
+    epilogue<false, FM>(acc, smem, C, ldc, w, wave, lane);
 }
 
 static int cus_per_xcd() {
@@ -428,59 +439,69 @@ static int set_smem(Kernel k, int bytes) {
     return e == hipSuccess ? MOE_OK : hip_fail(e, "hipFuncSetAttribute");
 }
 
-int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
-                    const int32_t* starts, const int32_t* placement, int local_gpu, void* out,
-                    int32_t* plan, void* H, hipStream_t s) {
+// FMU / FMD: fragment rows per wavefront of the up / down projection (row tile = 128 * FM)
+template <int FMU, int FMD>
+static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
+                   const int32_t* starts, const int32_t* placement, int local_gpu, void* out,
+                   int32_t* plan, void* H, bool split_down, hipStream_t s) {
     static bool configured = false;
-    static bool split_down = true;
+    int rc;
     if (!configured) {
-        int rc;
-        if ((rc = set_smem(&ffn_bf16_kernel<true, false>, smem_bytes<true>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_kernel<false, false>, smem_bytes<false>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_kernel<false, true>, smem_bytes<false>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_fixup_kernel, smem_bytes<false>())) != MOE_OK) return rc;
-        const char* v = getenv("MOE_FFN_SPLIT");
-        if (v) split_down = atoi(v) != 0;
+        if ((rc = set_smem(&ffn_bf16_kernel<true, false, FMU>, smem_bytes<true, FMU>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_kernel<false, false, FMD>, smem_bytes<false, FMD>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_kernel<false, true, FMD>, smem_bytes<false, FMD>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_fixup_kernel<FMD>, smem_bytes<false, FMD>())) != MOE_OK) return rc;
         configured = true;
     }
-    int rc = launch_ffn_plan(counts, starts, placement, local_gpu, E, N, BM, BM, plan, s);
+    constexpr int BMU = Tile<FMU>::BM, BMD = Tile<FMD>::BM;
+    rc = launch_ffn_plan(counts, starts, placement, local_gpu, E, N, BMU, BMD, plan, s);
     if (rc != MOE_OK) return rc;
     const int cpx = cus_per_xcd();
-    const long long mt_max = (N + BM - 1) / BM + (E < N ? E : N);     // sum of ceil(n_e / BM) never exceeds this
     const size_t s13 = npad13(f) * d, s2 = npad2(d) * f, stride = s13 + s2;
     const uint16_t* Wp = (const uint16_t*)packed;
     // partial tiles live behind H in the workspace
     float* partials = (float*)((char*)H + round_up((size_t)N * f * 2, 256));
-    auto grid_for = [&](size_t npad, bool split) {
+    auto grid_for = [&](size_t npad, int bm, bool split) {
+        const long long mt_max = (N + bm - 1) / bm + (E < N ? E : N);     // sum of ceil(n_e / bm) never exceeds this
         const long long tiles = mt_max * (long long)(npad / BN);
         return (long long)kXcds * ((tiles + kXcds - 1) / kXcds + (split ? cpx : 0));
     };
     {
-        const long long grid = grid_for(npad13(f), false);
+        const long long grid = grid_for(npad13(f), BMU, false);
         if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
         LaunchTimer timer(MOE_K_FFN_UP, s);
-        hipLaunchKernelGGL((ffn_bf16_kernel<true, false>), dim3((unsigned)grid), dim3(kThreads), smem_bytes<true>(), s,
+        hipLaunchKernelGGL((ffn_bf16_kernel<true, false, FMU>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<true, FMU>()), s,
                            (const uint16_t*)a, Wp, stride, d, (int)npad13(f), (uint16_t*)H, f, plan, partials, cpx);
         if ((rc = check_launch("moe_expert_ffn_grouped up launch")) != MOE_OK) return rc;
     }
     {
-        const long long grid = grid_for(npad2(d), split_down);
+        const long long grid = grid_for(npad2(d), BMD, split_down);
         if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
         LaunchTimer timer(MOE_K_FFN_DOWN, s);
         if (split_down) {
-            hipLaunchKernelGGL((ffn_bf16_kernel<false, true>), dim3((unsigned)grid), dim3(kThreads), smem_bytes<false>(), s,
+            hipLaunchKernelGGL((ffn_bf16_kernel<false, true, FMD>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FMD>()), s,
                                (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx);
             if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
-            hipLaunchKernelGGL(ffn_bf16_fixup_kernel, dim3(kXcds * (cpx / 2)), dim3(kThreads), smem_bytes<false>(), s, f,
+            hipLaunchKernelGGL(ffn_bf16_fixup_kernel<FMD>, dim3(kXcds * (cpx / 2)), dim3(kThreads), (smem_bytes<false, FMD>()), s, f,
                                (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx);
             if ((rc = check_launch("moe_expert_ffn_grouped fix-up launch")) != MOE_OK) return rc;
         } else {
-            hipLaunchKernelGGL((ffn_bf16_kernel<false, false>), dim3((unsigned)grid), dim3(kThreads), smem_bytes<false>(), s,
+            hipLaunchKernelGGL((ffn_bf16_kernel<false, false, FMD>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FMD>()), s,
                                (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx);
             if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
         }
     }
     return MOE_OK;
+}
+
+int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
+                    const int32_t* starts, const int32_t* placement, int local_gpu, void* out,
+                    int32_t* plan, void* H, hipStream_t s) {
+    // Row tiles of 384 move about a sixth fewer bytes per flop than tiles of 256, but waste more on
+    // ragged buckets; bucket sizes are only known on the device, so the choice goes by the mean.
+    if ((long long)N >= 768ll * E)
+        return run_ffn<3, 3>(a, N, d, f, E, packed, counts, starts, placement, local_gpu, out, plan, H, true, s);
+    return run_ffn<2, 2>(a, N, d, f, E, packed, counts, starts, placement, local_gpu, out, plan, H, true, s);
 }
 
 }  // namespace moe

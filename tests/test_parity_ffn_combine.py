@@ -50,6 +50,9 @@ def gpu_ffn(lib, x, w1, w3, w2, idx, pl, G, local_gpu, dtype):
     ("bf16", 64, 128, 128, 8, 2, 1, -1),
     ("bf16", 900, 192, 64, 16, 4, 4, 3),
     ("bf16", 130, 64, 1408, 64, 6, 8, 2),
+    ("bf16", 1700, 128, 192, 2, 1, 1, -1),      # large mean bucket: the 384-row tile path
+    ("bf16", 3000, 256, 2048, 1, 1, 1, -1),     # 384-row tiles with a k-split tail in the down projection
+    ("bf16", 3000, 256, 2048, 8, 1, 2, 1),      # 256-row tiles with a k-split tail
 ])
 def test_ffn_matches_oracle(lib, dtype, T, d, f, E, k, G, local):
     x, w1, w3, w2, idx, pl = make_problem(T + d, T, d, f, E, k, G, dtype)
