@@ -219,6 +219,33 @@ int moe_transition_counts(const int32_t* idx_l, const int32_t* idx_l1,
                           int64_t* R, void* stream);
 
 /* ------------------------------------------------------------------------
+ * Placement evaluators: the inputs and objective terms of the paper's two ILPs
+ * (Section 3.2) for a GIVEN expert->GPU map.  The ILP solve is not part of
+ * this library.  All arrays are device memory; every call is one small kernel.
+ *
+ * moe_accumulate_counts: P[e] += expert_counts[e]; gathers P_{e,l} (ILP 1
+ *   input) over the batches of a profiling run.  P [E] int64, caller-zeroed.
+ *
+ * moe_placement_loads: Eq. 2, T_c[c] = sum over e with placement[e] == c of
+ *   P[e], for c in [0,G); and, when imbalance != NULL, one layer's term of
+ *   Eq. 1 with the mean of Eq. 3: sum_c |T_c - (sum_e P[e]) / G| in fp64.
+ *   T_c [G] int64 out, imbalance [1] double out.
+ *
+ * moe_placement_traffic: Eq. 9, C[c1][c2] = sum of R[e1][e2] over e1 with
+ *   placement_l[e1] == c1 and e2 with placement_l1[e2] == c2 (placement_l is
+ *   layer l's map, placement_l1 layer l+1's).  When max_cost != NULL it also
+ *   gives one layer's term of Eq. 8 with clusters already on their GPUs:
+ *   max over GPU pairs of C[g1][g2] / B[g1][g2] (B == NULL: bandwidth 1).
+ *   R [E_l,E_l1] int64, C [G,G] int64 out, B [G,G] double, max_cost [1] double.
+ * ---------------------------------------------------------------------- */
+int moe_accumulate_counts(const int32_t* expert_counts, int E, int64_t* P, void* stream);
+int moe_placement_loads(const int64_t* P, const int32_t* placement, int E, int G,
+                        int64_t* T_c, double* imbalance, void* stream);
+int moe_placement_traffic(const int64_t* R, const int32_t* placement_l, const int32_t* placement_l1,
+                          int E_l, int E_l1, int G, int64_t* C, const double* B,
+                          double* max_cost, void* stream);
+
+/* ------------------------------------------------------------------------
  * Kernel timing.  Between moe_timing_begin and moe_timing_end every launch of
  * a kernel whose bit (1u << moe_kernel_id_t) is set in `mask` is bracketed by
  * a pair of HIP events on the stream it is launched on.  moe_timing_end

@@ -25,7 +25,8 @@ MOE_K_COUNT = len(KERNEL_NAMES)
 
 EXPORTS = ["moe_last_error", "moe_version", "moe_topk_gate", "moe_dispatch_workspace_bytes", "moe_dispatch",
            "moe_packed_weights_bytes", "moe_pack_weights", "moe_ffn_workspace_bytes", "moe_expert_ffn_grouped",
-           "moe_combine", "moe_transition_counts", "moe_timing_begin", "moe_timing_end"]
+           "moe_combine", "moe_transition_counts", "moe_accumulate_counts", "moe_placement_loads",
+           "moe_placement_traffic", "moe_timing_begin", "moe_timing_end"]
 
 
 class MoeError(RuntimeError):
@@ -54,6 +55,9 @@ _lib.moe_ffn_workspace_bytes.restype = _sz
 _lib.moe_expert_ffn_grouped.argtypes = [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]
 _lib.moe_combine.argtypes = [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
 _lib.moe_transition_counts.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
+_lib.moe_accumulate_counts.argtypes = [_vp, _i, _vp, _vp]
+_lib.moe_placement_loads.argtypes = [_vp, _vp, _i, _i, _vp, _vp, _vp]
+_lib.moe_placement_traffic.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp]
 _lib.moe_timing_begin.argtypes = [ctypes.c_uint, _i]
 _lib.moe_timing_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
 
@@ -145,6 +149,22 @@ def moe_combine(ffn_out, dt, inv_perm, topk_idx, topk_w, placement, local_gpu, T
 def moe_transition_counts(idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1, R):
     _dev(idx_l, idx_l1, R)
     _check(_lib.moe_transition_counts(_ptr(idx_l), _ptr(idx_l1), T, k_l, k_l1, E_l, E_l1, _ptr(R), _stream()))
+
+
+def moe_accumulate_counts(expert_counts, E, P):
+    _dev(expert_counts, P)
+    _check(_lib.moe_accumulate_counts(_ptr(expert_counts), E, _ptr(P), _stream()))
+
+
+def moe_placement_loads(P, placement, E, G, T_c, imbalance):
+    _dev(P, placement, T_c, imbalance)
+    _check(_lib.moe_placement_loads(_ptr(P), _ptr(placement), E, G, _ptr(T_c), _ptr(imbalance), _stream()))
+
+
+def moe_placement_traffic(R, placement_l, placement_l1, E_l, E_l1, G, C, B, max_cost):
+    _dev(R, placement_l, placement_l1, C, B, max_cost)
+    _check(_lib.moe_placement_traffic(_ptr(R), _ptr(placement_l), _ptr(placement_l1), E_l, E_l1, G, _ptr(C), _ptr(B),
+                                      _ptr(max_cost), _stream()))
 
 
 def moe_timing_begin(mask: int, max_records: int) -> None:

@@ -230,4 +230,26 @@ int moe_transition_counts(const int32_t* idx_l, const int32_t* idx_l1, int T, in
     return launch_transition(idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1, R, (hipStream_t)stream);
 }
 
+int moe_accumulate_counts(const int32_t* expert_counts, int E, int64_t* P, void* stream) {
+    REQUIRE(E >= 1 && E <= MOE_MAX_EXPERTS, "moe_accumulate_counts: E=%d outside [1,%d]", E, MOE_MAX_EXPERTS);
+    REQUIRE(expert_counts && P, "moe_accumulate_counts: NULL pointer");
+    return launch_accumulate_counts(expert_counts, E, P, (hipStream_t)stream);
+}
+
+int moe_placement_loads(const int64_t* P, const int32_t* placement, int E, int G, int64_t* T_c, double* imbalance, void* stream) {
+    REQUIRE(E >= 1 && E <= MOE_MAX_EXPERTS, "moe_placement_loads: E=%d outside [1,%d]", E, MOE_MAX_EXPERTS);
+    REQUIRE(G >= 1 && G <= MOE_MAX_GPUS, "moe_placement_loads: G=%d outside [1,%d]", G, MOE_MAX_GPUS);
+    REQUIRE(P && placement && T_c, "moe_placement_loads: NULL pointer");
+    return launch_placement_loads(P, placement, E, G, T_c, imbalance, (hipStream_t)stream);
+}
+
+int moe_placement_traffic(const int64_t* R, const int32_t* placement_l, const int32_t* placement_l1, int E_l, int E_l1, int G,
+                          int64_t* C, const double* B, double* max_cost, void* stream) {
+    REQUIRE(E_l >= 1 && E_l <= MOE_MAX_EXPERTS && E_l1 >= 1 && E_l1 <= MOE_MAX_EXPERTS,
+            "moe_placement_traffic: E_l=%d, E_l1=%d outside [1,%d]", E_l, E_l1, MOE_MAX_EXPERTS);
+    REQUIRE(G >= 1 && G <= MOE_MAX_GPUS, "moe_placement_traffic: G=%d outside [1,%d]", G, MOE_MAX_GPUS);
+    REQUIRE(R && placement_l && placement_l1 && C, "moe_placement_traffic: NULL pointer");
+    return launch_placement_traffic(R, placement_l, placement_l1, E_l, E_l1, G, C, B, max_cost, (hipStream_t)stream);
+}
+
 }  // extern "C"

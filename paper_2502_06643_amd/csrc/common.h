@@ -52,6 +52,11 @@ int launch_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm,
 int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_l, int k_l1, int E_l,
                       int E_l1, int64_t* R, hipStream_t s);
 
+int launch_accumulate_counts(const int32_t* counts, int E, int64_t* P, hipStream_t s);
+int launch_placement_loads(const int64_t* P, const int32_t* placement, int E, int G, int64_t* T_c, double* imbalance, hipStream_t s);
+int launch_placement_traffic(const int64_t* R, const int32_t* pl_l, const int32_t* pl_l1, int E_l, int E_l1, int G, int64_t* C,
+                             const double* B, double* max_cost, hipStream_t s);
+
 // FFN: the workspace starts with a small plan area, followed by H [N,f].
 constexpr size_t kPlanBytes = 8192;
 size_t packed_bytes_f32(int E, int d, int f);
