@@ -89,18 +89,20 @@ __global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(int32_t* __
         const int me = threadIdx.x;
         int start = 0;
         const int ge = pl[me];
+#pragma unroll 8
         for (int o = 0; o < E; ++o) {
             const int go = pl[o];
-            if (go < ge || (go == ge && o < me)) start += tot[o];
+            start += ((go < ge) | ((go == ge) & (o < me))) ? tot[o] : 0;
         }
         expert_start[me] = start;
     }
     for (int g = threadIdx.x; g < G; g += kScanThreads) {
         int cnt = 0, off = 0;
+#pragma unroll 8
         for (int o = 0; o < E; ++o) {
-            const int go = pl[o];
-            if (go == g) cnt += tot[o];
-            else if (go >= 0 && go < g) off += tot[o];
+            const int go = pl[o], to = tot[o];
+            cnt += (go == g) ? to : 0;
+            off += ((go >= 0) & (go < g)) ? to : 0;
         }
         gpu_counts[g] = cnt;
         gpu_offsets[g] = off;

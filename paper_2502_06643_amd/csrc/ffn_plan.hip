@@ -7,6 +7,8 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
                                                        int bm0, int bm1, int32_t* __restrict__ plan) {
     __shared__ int cnt[MOE_MAX_EXPERTS];
     __shared__ int rank[MOE_MAX_EXPERTS];
+    __shared__ int tiles0[MOE_MAX_EXPERTS];
+    __shared__ int tiles1[MOE_MAX_EXPERTS];
     const int e = threadIdx.x;
     int c = 0, st = 0;
     if (e < E) {
@@ -17,20 +19,28 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
         if (!local || c <= 0 || st < 0 || (long long)st + c > N) c = 0;
     }
     cnt[e] = c;
+    tiles0[e] = (c + bm0 - 1) / bm0;
+    tiles1[e] = (c + bm1 - 1) / bm1;
     __syncthreads();
     int r = 0;
-    if (c > 0)
-        for (int o = 0; o < E; ++o)
-            if (cnt[o] > c || (cnt[o] == c && o < e)) ++r;
+    if (c > 0) {
+#pragma unroll 8
+        for (int o = 0; o < E; ++o) {
+            const int co = cnt[o];
+            r += (co > c) | ((co == c) & (o < e));
+        }
+    }
     rank[e] = (c > 0) ? r : -1;
     __syncthreads();
     if (c > 0) {
         int t0 = 0, t1 = 0;
-        for (int o = 0; o < E; ++o)
-            if (rank[o] >= 0 && rank[o] < r) {
-                t0 += (cnt[o] + bm0 - 1) / bm0;
-                t1 += (cnt[o] + bm1 - 1) / bm1;
-            }
+#pragma unroll 8
+        for (int o = 0; o < E; ++o) {
+            const int ro = rank[o];
+            const int take = (ro >= 0) & (ro < r);
+            t0 += take ? tiles0[o] : 0;
+            t1 += take ? tiles1[o] : 0;
+        }
         plan[kPlanExpert + r] = e;
         plan[kPlanStart + r] = st;
         plan[kPlanCount + r] = c;
@@ -39,12 +49,12 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
     }
     if (e == 0) {
         int n = 0, t0 = 0, t1 = 0;
-        for (int o = 0; o < E; ++o)
-            if (cnt[o] > 0) {
-                ++n;
-                t0 += (cnt[o] + bm0 - 1) / bm0;
-                t1 += (cnt[o] + bm1 - 1) / bm1;
-            }
+#pragma unroll 8
+        for (int o = 0; o < E; ++o) {
+            n += cnt[o] > 0;
+            t0 += tiles0[o];
+            t1 += tiles1[o];
+        }
         plan[0] = n;
         plan[1] = t0;
         plan[2] = t1;
