@@ -39,6 +39,8 @@ import numpy as np
 
 __all__ = [
     "widen",
+    "router_logits",
+    "router_gate",
     "topk_gate",
     "dispatch",
     "expert_ffn_grouped",
@@ -77,6 +79,35 @@ def _check_index_array(name, a, lo, hi):
     if a.size and (a.min() < lo or a.max() >= hi):
         raise ValueError(f"{name} has entries outside [{lo}, {hi})")
     return a.astype(np.int64)
+
+
+# --------------------------------------------------------------------------
+# router projection (the step in front of the gate)
+# --------------------------------------------------------------------------
+def router_logits(x, w_g, bias=None):
+    """Router logits of a linear router (Section 2.1 describes the router that
+    scores the experts for each token; the linear form is this repository's
+    reading, as in Mixtral):
+    logits[t, e] = sum_i x[t, i] * W_g[i, e] + bias[e], in fp64.
+    x [T,d], w_g [d,E] (fp32, fp64 or bf16 bits), bias [E] or None."""
+    xa, wa = widen(x), widen(w_g)
+    if xa.ndim != 2 or wa.ndim != 2 or xa.shape[1] != wa.shape[0]:
+        raise ValueError("x must be [T,d] and w_g [d,E]")
+    lg = xa @ wa
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64)
+        if b.shape != (wa.shape[1],):
+            raise ValueError("bias must be [E]")
+        lg = lg + b[None, :]
+    return lg
+
+
+def router_gate(x, w_g, bias, k: int):
+    """router_logits followed by topk_gate, all in fp64.
+    Returns (logits float64 [T,E], topk_idx int32 [T,k], topk_w float64 [T,k])."""
+    lg = router_logits(x, w_g, bias)
+    idx, w = topk_gate(lg, k)
+    return lg, idx, w
 
 
 # --------------------------------------------------------------------------
