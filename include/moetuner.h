@@ -74,7 +74,8 @@ typedef enum {
     MOE_K_FFN_DOWN = 7,        /* H.W2                                        */
     MOE_K_COMBINE = 8,
     MOE_K_TRANSITION = 9,
-    MOE_K_COUNT = 10
+    MOE_K_ROUTER = 10,         /* x.W_g + bias of moe_router_gate              */
+    MOE_K_COUNT = 11
 } moe_kernel_id_t;
 
 /* Thread-local description of the last failure on this thread; never NULL. */
@@ -99,6 +100,31 @@ const char* moe_version(void);
  * ---------------------------------------------------------------------- */
 int moe_topk_gate(const float* logits, int T, int E, int k,
                   int32_t* topk_idx, float* topk_w, void* stream);
+
+/* ------------------------------------------------------------------------
+ * moe_router_gate - the linear router in front of the gate (Section 2.1):
+ *   logits[t][e] = sum_i x[t][i] * W_g[i][e] + bias[e],   then moe_topk_gate.
+ *
+ *   x        [T,d] dt
+ *   packed_router     W_g [d,E] re-laid out once by moe_pack_router (opaque,
+ *                     >= moe_router_packed_bytes(d,E,dt) bytes)
+ *   bias     [E] float, or NULL
+ *   logits   [T,E] float  out (required: the selection reads it back)
+ *   topk_idx, topk_w      as in moe_topk_gate
+ *
+ * MOE_BF16: bf16 inputs, fp32 accumulation in a fixed order; requires
+ * d % 64 == 0.  MOE_F32: fp32 throughout.  Because the logits are rounded
+ * differently than an exact product, a token whose k-th and (k+1)-th logits are
+ * closer than that rounding may legitimately select the other expert.
+ * ---------------------------------------------------------------------- */
+size_t moe_router_packed_bytes(int d, int E, moe_dtype_t dt);
+
+int moe_pack_router(const void* w_g /*[d,E] dt*/, int d, int E, moe_dtype_t dt,
+                    void* packed, size_t packed_bytes, void* stream);
+
+int moe_router_gate(const void* x, moe_dtype_t dt, const void* packed_router, const float* bias,
+                    int T, int d, int E, int k,
+                    float* logits, int32_t* topk_idx, float* topk_w, void* stream);
 
 /* ------------------------------------------------------------------------
  * moe_dispatch - placement-aware token dispatch (Section 1 and Section 2.2:

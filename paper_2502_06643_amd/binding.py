@@ -20,10 +20,10 @@ LIB_PATH = os.path.join(_HERE, "libmoetuner_hip.so")
 MOE_F32, MOE_BF16 = 0, 1
 MOE_MAX_EXPERTS, MOE_MAX_GPUS, MOE_MAX_TOPK = 256, 256, 16
 KERNEL_NAMES = ["gate", "dispatch_count", "dispatch_scan", "dispatch_rank", "dispatch_rows",
-                "ffn_plan", "ffn_up", "ffn_down", "combine", "transition"]
+                "ffn_plan", "ffn_up", "ffn_down", "combine", "transition", "router"]
 MOE_K_COUNT = len(KERNEL_NAMES)
 
-EXPORTS = ["moe_last_error", "moe_version", "moe_topk_gate", "moe_dispatch_workspace_bytes", "moe_dispatch",
+EXPORTS = ["moe_last_error", "moe_version", "moe_topk_gate", "moe_router_packed_bytes", "moe_pack_router", "moe_router_gate", "moe_dispatch_workspace_bytes", "moe_dispatch",
            "moe_packed_weights_bytes", "moe_pack_weights", "moe_ffn_workspace_bytes", "moe_expert_ffn_grouped",
            "moe_combine", "moe_transition_counts", "moe_accumulate_counts", "moe_placement_loads",
            "moe_placement_traffic", "moe_timing_begin", "moe_timing_end"]
@@ -44,6 +44,10 @@ _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 _lib.moe_last_error.restype = ctypes.c_char_p
 _lib.moe_version.restype = ctypes.c_char_p
 _lib.moe_topk_gate.argtypes = [_vp, _i, _i, _i, _vp, _vp, _vp]
+_lib.moe_router_packed_bytes.argtypes = [_i, _i, _i]
+_lib.moe_router_packed_bytes.restype = _sz
+_lib.moe_pack_router.argtypes = [_vp, _i, _i, _i, _vp, _sz, _vp]
+_lib.moe_router_gate.argtypes = [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
 _lib.moe_dispatch_workspace_bytes.argtypes = [_i, _i, _i]
 _lib.moe_dispatch_workspace_bytes.restype = _sz
 _lib.moe_dispatch.argtypes = [_vp, _i, _vp, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -104,6 +108,21 @@ def moe_last_error() -> str:
 def moe_topk_gate(logits, T, E, k, topk_idx, topk_w):
     _dev(logits, topk_idx, topk_w)
     _check(_lib.moe_topk_gate(_ptr(logits), T, E, k, _ptr(topk_idx), _ptr(topk_w), _stream()))
+
+
+def moe_router_packed_bytes(d, E, dt) -> int:
+    return _lib.moe_router_packed_bytes(d, E, dt)
+
+
+def moe_pack_router(w_g, d, E, dt, packed):
+    _dev(w_g, packed)
+    _check(_lib.moe_pack_router(_ptr(w_g), d, E, dt, _ptr(packed), packed.numel() * packed.element_size(), _stream()))
+
+
+def moe_router_gate(x, dt, packed_router, bias, T, d, E, k, logits, topk_idx, topk_w):
+    _dev(x, packed_router, bias, logits, topk_idx, topk_w)
+    _check(_lib.moe_router_gate(_ptr(x), dt, _ptr(packed_router), _ptr(bias), T, d, E, k, _ptr(logits), _ptr(topk_idx),
+                                _ptr(topk_w), _stream()))
 
 
 def moe_dispatch_workspace_bytes(T, E, k) -> int:

@@ -105,6 +105,43 @@ int moe_topk_gate(const float* logits, int T, int E, int k, int32_t* topk_idx, f
     return launch_gate(logits, T, E, k, topk_idx, topk_w, (hipStream_t)stream);
 }
 
+static int check_router_shape(const char* who, int d, int E, moe_dtype_t dt) {
+    REQUIRE(dt == MOE_F32 || dt == MOE_BF16, "%s: unknown dtype %d", who, (int)dt);
+    REQUIRE(E >= 1 && E <= MOE_MAX_EXPERTS, "%s: E=%d outside [1,%d]", who, E, MOE_MAX_EXPERTS);
+    REQUIRE(d >= 1, "%s: d=%d < 1", who, d);
+    if (dt == MOE_BF16 && d % 64) return fail(MOE_ERR_UNSUPPORTED, "%s: bf16 needs d %% 64 == 0 (d=%d)", who, d);
+    return MOE_OK;
+}
+
+size_t moe_router_packed_bytes(int d, int E, moe_dtype_t dt) {
+    if (check_router_shape("moe_router_packed_bytes", d, E, dt) != MOE_OK) return 0;
+    return router_packed_bytes(d, E, dt);
+}
+
+int moe_pack_router(const void* w_g, int d, int E, moe_dtype_t dt, void* packed, size_t packed_bytes, void* stream) {
+    int rc = check_router_shape("moe_pack_router", d, E, dt);
+    if (rc != MOE_OK) return rc;
+    REQUIRE(w_g && packed, "moe_pack_router: NULL pointer");
+    REQUIRE(aligned16(w_g) && aligned16(packed), "moe_pack_router: pointers must be 16-byte aligned");
+    if (packed_bytes < router_packed_bytes(d, E, dt))
+        return fail(MOE_ERR_WORKSPACE, "moe_pack_router: packed buffer %zu < %zu bytes", packed_bytes, router_packed_bytes(d, E, dt));
+    return launch_pack_router(w_g, d, E, dt, packed, (hipStream_t)stream);
+}
+
+int moe_router_gate(const void* x, moe_dtype_t dt, const void* packed_router, const float* bias, int T, int d, int E, int k,
+                    float* logits, int32_t* topk_idx, float* topk_w, void* stream) {
+    int rc = check_router_shape("moe_router_gate", d, E, dt);
+    if (rc != MOE_OK) return rc;
+    REQUIRE(T >= 0, "moe_router_gate: T=%d < 0", T);
+    REQUIRE(k >= 1 && k <= E && k <= MOE_MAX_TOPK, "moe_router_gate: k=%d outside [1,min(E=%d,%d)]", k, E, MOE_MAX_TOPK);
+    REQUIRE((long long)T * E < (1ll << 31), "moe_router_gate: T*E too large");
+    if (T == 0) return MOE_OK;
+    REQUIRE(x && packed_router && logits && topk_idx && topk_w, "moe_router_gate: NULL pointer");
+    REQUIRE(aligned16(x) && aligned16(packed_router) && aligned16(logits) && aligned16(topk_idx) && aligned16(topk_w),
+            "moe_router_gate: pointers must be 16-byte aligned");
+    return launch_router_gate(x, dt, packed_router, bias, T, d, E, k, logits, topk_idx, topk_w, (hipStream_t)stream);
+}
+
 size_t moe_dispatch_workspace_bytes(int T, int E, int k) {
     if (T < 0 || E < 1 || k < 1) return 0;
     int items = 0, nb = 0;

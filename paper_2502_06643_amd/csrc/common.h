@@ -52,6 +52,10 @@ int launch_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm,
 int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_l, int k_l1, int E_l,
                       int E_l1, int64_t* R, hipStream_t s);
 
+size_t router_packed_bytes(int d, int E, moe_dtype_t dt);
+int launch_pack_router(const void* w_g, int d, int E, moe_dtype_t dt, void* packed, hipStream_t s);
+int launch_router_gate(const void* x, moe_dtype_t dt, const void* packed, const float* bias, int T, int d, int E, int k,
+                       float* logits, int32_t* idx, float* w, hipStream_t s);
 int launch_accumulate_counts(const int32_t* counts, int E, int64_t* P, hipStream_t s);
 int launch_placement_loads(const int64_t* P, const int32_t* placement, int E, int G, int64_t* T_c, double* imbalance, hipStream_t s);
 int launch_placement_traffic(const int64_t* R, const int32_t* pl_l, const int32_t* pl_l1, int E_l, int E_l1, int G, int64_t* C,

@@ -1,0 +1,76 @@
+"""GPU parity: moe_router_gate (x . W_g + bias, then top-k) vs the fp64 oracle.
+
+The logits are floating point (fp32 accumulation on the GPU, fp64 in the
+oracle): they must agree within 1e-5 of the row scale.  The selected experts
+are decided by those logits, so they can only be required to match where the
+decision is not within the rounding of the logits: a token whose relevant
+logits (the top k+1) are all further apart than the margin must match exactly;
+for the others the GPU's choice must still be a valid top-k up to the margin.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2502_06643_amd import synth
+from paper_2502_06643_amd.layer import to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def run_router(lib, x, w_g, bias, k):
+    T, d = x.shape
+    E = w_g.shape[1]
+    dt = lib.MOE_BF16 if x.dtype == np.uint16 else lib.MOE_F32
+    packed = torch.empty(lib.moe_router_packed_bytes(d, E, dt), dtype=torch.uint8, device="cuda")
+    lib.moe_pack_router(to_device(w_g), d, E, dt, packed)
+    logits = torch.full((T, E), 7.0, dtype=torch.float32, device="cuda")
+    idx = torch.full((T, k), -1, dtype=torch.int32, device="cuda")
+    w = torch.full((T, k), -1.0, dtype=torch.float32, device="cuda")
+    b = None if bias is None else torch.from_numpy(np.asarray(bias, dtype=np.float32)).cuda()
+    lib.moe_router_gate(to_device(x), dt, packed, b, T, d, E, k, logits, idx, w)
+    torch.cuda.synchronize()
+    return logits.cpu().numpy(), idx.cpu().numpy(), w.cpu().numpy()
+
+
+def check(lib, x, w_g, bias, k):
+    bias32 = None if bias is None else np.asarray(bias, dtype=np.float32)       # the GPU receives an fp32 bias
+    lg_ref, idx_ref, w_ref = O.router_gate(x, w_g, bias32, k)
+    lg, idx, w = run_router(lib, x, w_g, bias, k)
+    T, E = lg_ref.shape
+    scale = np.sqrt(np.mean(lg_ref ** 2, axis=1, keepdims=True)) + 1e-30
+    err = np.max(np.abs(lg - lg_ref) / np.maximum(np.abs(lg_ref), scale))
+    assert err <= 1e-5, err
+    margin = 2e-5 * scale[:, 0]
+    srt = -np.sort(-lg_ref, axis=1)
+    gaps = srt[:, :min(k, E - 1)] - srt[:, 1:min(k, E - 1) + 1]                 # gaps that decide the selection and its order
+    clear = np.all(gaps > margin[:, None], axis=1)
+    assert clear.mean() > 0.9
+    np.testing.assert_array_equal(idx[clear], idx_ref[clear])
+    wrel = np.abs(w[clear] - w_ref[clear]) / np.maximum(w_ref[clear], 1e-30)
+    assert wrel.max() <= 2e-3 if clear.any() else True                          # exp amplifies the logit rounding a little
+    for t in np.nonzero(~clear)[0]:                                              # near ties: any selection within the margin is right
+        chosen = lg_ref[t, idx[t]]
+        assert len(set(idx[t].tolist())) == k
+        assert chosen.min() >= srt[t, k - 1] - margin[t]
+    return err, float(clear.mean())
+
+
+@pytest.mark.parametrize("name", ["c1", "c1b", "c2", "c4", "c3"])
+def test_config_routers(lib, name):
+    cfg = synth.config(name)
+    x = synth.make_x(cfg)
+    w_g, bias = synth.make_router(cfg)
+    err, clear = check(lib, x, w_g, bias, cfg.k)
+    print(f"{name}: max logit error {err:.2e}, tokens with a clear decision {clear:.4f}")
+
+
+@pytest.mark.parametrize("dtype,T,d,E,k", [("bf16", 1, 64, 8, 2), ("bf16", 33, 128, 5, 5), ("bf16", 1000, 512, 130, 4),
+                                            ("bf16", 257, 256, 256, 16), ("bf16", 95, 192, 33, 3), ("f32", 100, 36, 7, 3),
+                                            ("f32", 300, 128, 256, 8)])
+def test_other_shapes(lib, dtype, T, d, E, k):
+    x = synth.normal(T + E, 0, (T, d), 1.0, dtype)
+    w_g = synth.normal(T + E, 1, (d, E), 1.0 / np.sqrt(d), dtype)
+    bias = np.random.default_rng(E).standard_normal(E)
+    check(lib, x, w_g, bias, k)
+    check(lib, x, w_g, None, k)
