@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # Bytes that cross the L2 boundary per launch of the dominant kernel (up projection), from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain 1 GiB copy of known size; the summary
 # and the commands are in profiles/bench_c2_rocprofv3.md.  Only known for the default workload.
-MEASURED_TRAFFIC_BYTES = {"c2": 5027.4e6 + 234.9e6}
+MEASURED_TRAFFIC_BYTES = {"c2": 3982.9e6 + 234.9e6}
 
 
 def cpu_baseline(cfg, x, lg, weights, pl, budget_rows=8192):
@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="override the workload's token count T (scaled shapes for the bandwidth-bound kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -103,6 +105,8 @@ def main():
     torch.cuda.set_device(0)
 
     cfg = synth.config(args.workload)
+    if args.tokens > 0:
+        cfg = cfg.with_(T=args.tokens, name=f"{cfg.name}@T={args.tokens}")
     x = synth.make_x(cfg)
     lg = synth.make_logits(cfg, x)
     weights = synth.make_expert_weights(cfg)
