@@ -105,6 +105,7 @@ int launch_ffn_f32(const float* a, int N, int d, int f, int E, const float* pack
     int rc = launch_ffn_plan(counts, starts, placement, local_gpu, E, N, FBM, FBM, plan, s);
     if (rc != MOE_OK) return rc;
     const int mt_max = (N + FBM - 1) / FBM + (E < N ? E : N);     // sum of ceil(n_e/BM) never exceeds this
+    if (mt_max > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: fp32 path supports at most %d routes", (65535 - 256) * FBM);
     {
         LaunchTimer timer(MOE_K_FFN_UP, s);
         hipLaunchKernelGGL(ffn_f32_kernel<true>, dim3((f + FBN - 1) / FBN, mt_max), dim3(256), 0, s, a, packed, d, f, H, plan);

@@ -82,6 +82,33 @@ def test_ffn_skewed_buckets_including_empty_and_single_row_experts(lib):
     assert rel_err(as_f64(to_host(L.ffn_out)), ref) <= TOL_BF16
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ffn_when_this_gpu_owns_no_expert_or_no_route(lib, dtype):
+    """local_gpu owns no expert (the ILP forbids it, the library tolerates it), and a GPU whose experts got no route:
+    nothing may be written and nothing may fault."""
+    x, w1, w3, w2, idx, pl = make_problem(11, 200, 128, 128, 4, 1, 2, dtype)
+    pl[:] = 0                                                # GPU 1 owns nothing
+    L = gpu_ffn(lib, x, w1, w3, w2, idx, pl, 2, 1, dtype)
+    assert torch.all(L.ffn_out.float() == 7.0)
+    pl = np.array([0, 0, 0, 1], dtype=np.int32)
+    idx = np.minimum(idx, 2)                                 # expert 3 (GPU 1's only one) receives nothing
+    L = gpu_ffn(lib, x, w1, w3, w2, idx, pl, 2, 1, dtype)
+    assert torch.all(L.ffn_out.float() == 7.0)
+
+
+def test_ffn_with_the_maximum_number_of_experts(lib):
+    T, d, f, E, k = 900, 64, 64, 256, 16
+    x, w1, w3, w2, idx, pl = make_problem(12, T, d, f, E, k, 16, "bf16")
+    L = gpu_ffn(lib, x, w1, w3, w2, idx, pl, 16, 5, "bf16")
+    dsp = O.dispatch(x, idx, pl, 16)
+    ref = O.expert_ffn_grouped(dsp["send_buf"], w1, w3, w2, dsp["expert_counts"], dsp["expert_start"], pl, 5)
+    e_sorted = idx.reshape(-1)[dsp["perm"]]
+    loc = pl[e_sorted] == 5
+    got = as_f64(to_host(L.ffn_out))
+    assert loc.any() and rel_err(got[loc], ref[loc]) <= TOL_BF16
+    assert np.all(got[~loc] == 7.0)
+
+
 @pytest.mark.parametrize("dtype,local", [("f32", -1), ("f32", 1), ("bf16", -1), ("bf16", 2)])
 def test_combine_matches_oracle(lib, dtype, local):
     T, d, E, k, G = 777, 256, 8, 3, 4
