@@ -62,6 +62,7 @@ constexpr int WM = 4, WN = 2, NW = WM * WN;     // wavefront grid
 constexpr int WTN = BN / WN;                    // 128 columns per wavefront
 constexpr int FN = WTN / 32;                    // 4 column fragments of 32
 constexpr int NS = 2;                           // LDS stages
+constexpr int kDmaEvery = 2;                    // matrix instructions between two direct-to-LDS loads of the next k tile
 constexpr int KB = BK / 16;                     // k-blocks per stage
 constexpr int B_CHUNKS = BN / 8;                // 1 KB pieces of the weight tile per stage
 constexpr int B_PER_WAVE = B_CHUNKS / NW;
@@ -205,76 +206,130 @@ __device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
+// Rows of a tile are dealt to the four wavefront rows in blocks of 32: fragment a of wavefront row m
+// covers tile rows 32 * (4a + m) .. +31.  A ragged tile of r rows then keeps every SIMD equally busy
+// and costs ceil(r / 128) fragment rows of matrix work instead of the whole tile.
+__device__ __forceinline__ int frag_row(int a, int wave_m) { return (a * WM + wave_m) * 32; }
+__device__ __forceinline__ int active_frags(int rows, int wave_m, int fm) {
+    const int n = (rows - wave_m * 32 + 32 * WM - 1) / (32 * WM);
+    return n < 0 ? 0 : (n > fm ? fm : n);
+}
+
+// what a wavefront needs to fetch its share of a k tile: per-lane byte offsets of its 1 KB pieces
+// (the k tile moves the scalar base) and the LDS address of its first piece in stage 0
+template <int FM>
+struct Loader {
+    uint32_t a_voff[Tile<FM>::A_PER_WAVE], b_voff[B_PER_WAVE];
+    const uint16_t* Abase;
+    const uint16_t* Bbase;
+    uint32_t lds;
+    static constexpr int N_DMA = Tile<FM>::A_PER_WAVE + B_PER_WAVE;
+    // piece j of k tile kt: first the activation pieces, then the weight pieces
+    __device__ __forceinline__ void issue(int j, int kt, int stage) const {
+        const uint32_t l = lds + (uint32_t)stage * (Tile<FM>::STAGE * 2);
+        if (j < Tile<FM>::A_PER_WAVE) dma16(a_voff[j], Abase + (size_t)kt * BK, l + j * NW * 1024);
+        else dma16(b_voff[j - Tile<FM>::A_PER_WAVE], Bbase + (size_t)kt * (BK * BN),
+                   l + (Tile<FM>::A_CHUNKS + (j - Tile<FM>::A_PER_WAVE) * NW) * 1024);
+    }
+};
+
+// One k tile of matrix instructions for a wavefront with NF active fragment rows.  With `load`, the
+// pieces of the next k tile are issued one at a time between groups of kDmaEvery matrix instructions:
+// the memory pipeline takes 16 cycles per 1 KB piece, and a wavefront that issues its pieces back to
+// back sits in the issue stage for that long while its matrix instructions wait behind them.  Pieces
+// that find no slot (few active fragments) go first.
+template <int FM, int NF>
+__device__ __forceinline__ void ktile(f32x16 (&acc)[FM][FN], const uint16_t* As, const Loader<FM>& ld, int kt, int stage,
+                                      bool load, int wave_m, int wave_n, int lane) {
+    constexpr int BM = Tile<FM>::BM, N_DMA = Loader<FM>::N_DMA;
+    constexpr int SLOTS = KB * NF * FN / kDmaEvery;
+    constexpr int UPFRONT = N_DMA > SLOTS ? N_DMA - SLOTS : 0;
+    const uint16_t* Bs = As + BM * BK;
+    if (UPFRONT > 0 && load) {
+#pragma unroll
+        for (int j = 0; j < UPFRONT; ++j) ld.issue(j, kt + 1, stage ^ 1);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KB; ++ks) {
+        bf16x8 af[NF], bfr[FN];
+#pragma unroll
+        for (int a = 0; a < NF; ++a) {
+            const int r = frag_row(a, wave_m) + (lane & 31);
+            af[a] = *reinterpret_cast<const bf16x8*>(As + r * BK + swz(r, ks * 2 + (lane >> 5)) * 8);
+        }
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+            bfr[b] = *reinterpret_cast<const bf16x8*>(Bs + ((wave_n * FN + b) * KB + ks) * 512 + lane * 8);
+#pragma unroll
+        for (int a = 0; a < NF; ++a)
+#pragma unroll
+            for (int b = 0; b < FN; ++b) {
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+                const int m = (ks * NF + a) * FN + b;
+                if (m % kDmaEvery == kDmaEvery - 1 && UPFRONT + m / kDmaEvery < N_DMA) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (load) ld.issue(UPFRONT + m / kDmaEvery, kt + 1, stage ^ 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+    }
+}
+
+// the k loop of a wavefront with NF active fragment rows (NF = 0: it only fetches its share of the tiles)
+template <int FM, int NF>
+__device__ __forceinline__ void kloop(f32x16 (&acc)[FM][FN], const uint16_t* smem, const Loader<FM>& ld, const WorkItem& w,
+                                      int wave_m, int wave_n, int lane) {
+    constexpr int STAGE = Tile<FM>::STAGE, N_DMA = Loader<FM>::N_DMA;
+    int stage = 0;
+    for (int kt = w.kt0; kt < w.kt1; ++kt) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wavefront's pieces of tile kt have landed
+        __syncthreads();                                     // everyone's have, and tile kt-1 has been consumed
+        const bool more = kt + 1 < w.kt1;
+        if (NF > 0) {
+            ktile<FM, (NF > 0 ? NF : 1)>(acc, smem + stage * STAGE, ld, kt, stage, more, wave_m, wave_n, lane);
+        } else if (more) {
+#pragma unroll
+            for (int j = 0; j < N_DMA; ++j) ld.issue(j, kt + 1, stage ^ 1);
+        }
+        stage ^= 1;
+    }
+}
+
 // acc += A[row0 .. row0+rows, k tiles kt0..kt1) * B(tile), everything through LDS
 template <int FM>
 __device__ __forceinline__ void mainloop(f32x16 (&acc)[FM][FN], uint16_t* smem, const uint16_t* __restrict__ A,
                                          const uint16_t* __restrict__ Bbase, int K, const WorkItem& w, int wave, int lane,
-                                         bool wave_active) {
-    constexpr int WTM = Tile<FM>::WTM, BM = Tile<FM>::BM, STAGE = Tile<FM>::STAGE;
-    constexpr int A_CHUNKS = Tile<FM>::A_CHUNKS, A_PER_WAVE = Tile<FM>::A_PER_WAVE;
+                                         int nfrag) {
+    constexpr int A_PER_WAVE = Tile<FM>::A_PER_WAVE, N_DMA = Loader<FM>::N_DMA;
     const int wave_m = wave / WN, wave_n = wave % WN;
-    const uint16_t* Abase = A + (size_t)w.row0 * K;
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
-
-    // per-lane byte offsets of this wavefront's 1 KB pieces (the k tile moves the scalar base)
-    uint32_t a_voff[A_PER_WAVE], b_voff[B_PER_WAVE];
+    Loader<FM> ld;
+    ld.Abase = A + (size_t)w.row0 * K;
+    ld.Bbase = Bbase;
+    ld.lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem + (uint32_t)wave * 1024u;
 #pragma unroll
     for (int j = 0; j < A_PER_WAVE; ++j) {
         const int c = wave + j * NW;                         // rows 8c .. 8c+7
         const int r = c * 8 + (lane >> 3);
         const int g = swz(r, lane & 7);                      // global chunk that lands in LDS slot lane & 7
-        a_voff[j] = (uint32_t)min(r, w.rows - 1) * (uint32_t)K * 2u + (uint32_t)g * 16u;   // rows past the bucket re-read its last row
+        ld.a_voff[j] = (uint32_t)min(r, w.rows - 1) * (uint32_t)K * 2u + (uint32_t)g * 16u;   // rows past the bucket re-read its last row
     }
 #pragma unroll
-    for (int j = 0; j < B_PER_WAVE; ++j) b_voff[j] = (uint32_t)(wave + j * NW) * 1024u + (uint32_t)lane * 16u;
+    for (int j = 0; j < B_PER_WAVE; ++j) ld.b_voff[j] = (uint32_t)(wave + j * NW) * 1024u + (uint32_t)lane * 16u;
 
-    auto issue = [&](int kt, int stage) {
-        const uint16_t* ab = Abase + (size_t)kt * BK;
-        const uint16_t* bb = Bbase + (size_t)kt * (BK * BN);
-        const uint32_t l = lds0 + (uint32_t)stage * (STAGE * 2) + (uint32_t)wave * 1024u;
 #pragma unroll
-        for (int j = 0; j < A_PER_WAVE; ++j) dma16(a_voff[j], ab, l + j * NW * 1024);
-#pragma unroll
-        for (int j = 0; j < B_PER_WAVE; ++j) dma16(b_voff[j], bb, l + (A_CHUNKS + j * NW) * 1024);
-    };
-
-    issue(w.kt0, 0);
-    int stage = 0;
-    for (int kt = w.kt0; kt < w.kt1; ++kt) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wavefront's pieces of tile kt have landed
-        __syncthreads();                                     // everyone's have, and tile kt-1 has been consumed
-        if (kt + 1 < w.kt1) issue(kt + 1, stage ^ 1);
-        if (wave_active) {
-            const uint16_t* As = smem + stage * STAGE;
-            const uint16_t* Bs = As + BM * BK;
-#pragma unroll
-            for (int ks = 0; ks < KB; ++ks) {
-                bf16x8 af[FM], bfr[FN];
-#pragma unroll
-                for (int a = 0; a < FM; ++a) {
-                    const int r = wave_m * WTM + a * 32 + (lane & 31);
-                    af[a] = *reinterpret_cast<const bf16x8*>(As + r * BK + swz(r, ks * 2 + (lane >> 5)) * 8);
-                }
-#pragma unroll
-                for (int b = 0; b < FN; ++b)
-                    bfr[b] = *reinterpret_cast<const bf16x8*>(Bs + ((wave_n * FN + b) * KB + ks) * 512 + lane * 8);
-#pragma unroll
-                for (int a = 0; a < FM; ++a)
-#pragma unroll
-                    for (int b = 0; b < FN; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
-            }
-        }
-        stage ^= 1;
-    }
+    for (int j = 0; j < N_DMA; ++j) ld.issue(j, w.kt0, 0);
+    // one copy of the loop per number of active fragment rows: the accumulators of the others stay zero
+    if (nfrag == FM) kloop<FM, FM>(acc, smem, ld, w, wave_m, wave_n, lane);
+    else if (FM >= 2 && nfrag == FM - 1) kloop<FM, (FM >= 2 ? FM - 1 : 0)>(acc, smem, ld, w, wave_m, wave_n, lane);
+    else if (FM >= 3 && nfrag == FM - 2) kloop<FM, (FM >= 3 ? FM - 2 : 0)>(acc, smem, ld, w, wave_m, wave_n, lane);
+    else kloop<FM, 0>(acc, smem, ld, w, wave_m, wave_n, lane);
 }
 
 // accumulators -> bf16 -> per-wavefront LDS staging tile (32 rows at a time) -> 16-byte stores of
 // whole lines.  accumulator v of a 32x32 fragment: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
 template <bool UP, int FM>
 __device__ __forceinline__ void epilogue(const f32x16 (&acc)[FM][FN], uint16_t* smem, uint16_t* __restrict__ C, int ldc,
-                                         const WorkItem& w, int wave, int lane) {
-    constexpr int WTM = Tile<FM>::WTM;
+                                         const WorkItem& w, int wave, int lane, int nfrag) {
     constexpr int OUTC = UP ? WTN / 2 : WTN;          // output columns of this wavefront
     constexpr int RS = OUTC + 8;                      // staging row stride (elements); the pad staggers the banks
     constexpr int CPR = OUTC / 8;                     // 16-byte chunks per row
@@ -284,6 +339,7 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[FM][FN], uint16_t* 
     const int col = (UP ? w.nt * (BN / 2) : w.nt * BN) + wave_n * OUTC + (lane % CPR) * 8;
 #pragma unroll
     for (int a = 0; a < FM; ++a) {
+        if (a < nfrag) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -303,10 +359,11 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[FM][FN], uint16_t* 
 #pragma unroll
         for (int it = 0; it < 32 / RPI; ++it) {
             const int r = it * RPI + lane / CPR;
-            const int gr = wave_m * WTM + a * 32 + r;
+            const int gr = frag_row(a, wave_m) + r;
             if (gr < w.rows && col < ldc)
                 *reinterpret_cast<u32x4*>(C + (size_t)(w.row0 + gr) * ldc + col) =
                     *reinterpret_cast<const u32x4*>(stg + r * RS + (lane % CPR) * 8);
+        }
         }
     }
 }
@@ -324,7 +381,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
                                                             size_t expert_stride, int K, int npad, uint16_t* __restrict__ C,
                                                             int ldc, const int32_t* __restrict__ plan, float* __restrict__ partials,
                                                             int cus_per_xcd) {
-    constexpr int WTM = Tile<FM>::WTM, BM = Tile<FM>::BM;
+    constexpr int BM = Tile<FM>::BM;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int32_t* prefix = plan + (UP ? kPlanTiles0 : kPlanTiles1);
     const int NT = npad / BN, KT = K / BK;
@@ -347,7 +404,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool wave_active = (wave / WN) * WTM < w.rows;
+    const int nfrag = active_frags(w.rows, wave / WN, FM);    // fragment rows of this wavefront that hold rows of the bucket
     const uint16_t* Bbase = Wp + (size_t)w.expert * expert_stride + (size_t)w.nt * ((size_t)K * BN);
 
     f32x16 acc[FM][FN];
@@ -358,11 +415,12 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    mainloop<FM>(acc, smem, A, Bbase, K, w, wave, lane, wave_active);
+    mainloop<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag);
 
     if (SPLIT && w.partial >= 0) {
-        if (wave_active) {
-            // 16 bytes per lane and store: [fragment][quad of accumulators][thread]
+        if (nfrag > 0) {
+            // 16 bytes per lane and store: [fragment][quad of accumulators][thread]; fragments past the
+            // bucket's end hold zeros
             f32x4* dst = reinterpret_cast<f32x4*>(partials + (size_t)w.partial * Tile<FM>::kPartialFloats) + tid;
 #pragma unroll
             for (int a = 0; a < FM; ++a)
@@ -377,7 +435,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
         return;
     }
     __syncthreads();                                  // the last tile's fragments have been read by everyone
-    if (wave_active) epilogue<UP, FM>(acc, smem, C, ldc, w, wave, lane);
+    epilogue<UP, FM>(acc, smem, C, ldc, w, wave, lane, nfrag);
 }
 
 // adds the k parts of the split tail tiles in part order and writes the tiles
@@ -385,7 +443,7 @@ template <int FM>
 __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npad, uint16_t* __restrict__ C, int ldc,
                                                                   const int32_t* __restrict__ plan,
                                                                   const float* __restrict__ partials, int cus_per_xcd) {
-    constexpr int WTM = Tile<FM>::WTM, BM = Tile<FM>::BM;
+    constexpr int BM = Tile<FM>::BM;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int32_t* prefix = plan + kPlanTiles1;
     const int NT = npad / BN, KT = K / BK;
@@ -397,7 +455,8 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
     locate_tile(plan, prefix, NT, sh.t_begin + sh.full + q, BM, w);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if ((wave / WN) * WTM >= w.rows) return;
+    const int nfrag = active_frags(w.rows, wave / WN, FM);
+    if (nfrag == 0) return;
     f32x16 acc[FM][FN];
 #pragma unroll
     for (int a = 0; a < FM; ++a)
@@ -408,7 +467,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
     for (int part = 0; part < sh.split; ++part) {
         const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * cus_per_xcd + q * sh.split + part) * Tile<FM>::kPartialFloats) + tid;
 #pragma unroll
-        for (int a = 0; a < FM; ++a)
+        for (int a = 0; a < FM; ++a) {
 #pragma unroll
             for (int b = 0; b < FN; ++b)
 #pragma unroll
@@ -417,8 +476,10 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
                     acc[a][b][4 * g] += t[0]; acc[a][b][4 * g + 1] += t[1];
                     acc[a][b][4 * g + 2] += t[2]; acc[a][b][4 * g + 3] += t[3];
                 }
+            __builtin_amdgcn_sched_barrier(0);               // one fragment row of loads in flight at a time
+        }
     }
-    epilogue<false, FM>(acc, smem, C, ldc, w, wave, lane);
+    epilogue<false, FM>(acc, smem, C, ldc, w, wave, lane, nfrag);
 }
 
 static int cus_per_xcd() {
