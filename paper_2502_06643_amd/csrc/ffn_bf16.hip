@@ -6,37 +6,45 @@
 //
 // Work decomposition.  A workgroup of 8 wavefronts (4 along rows x 2 along
 // columns, two wavefronts per SIMD) owns one 256 x 256 output tile of one
-// expert (64 x 128 per wavefront), or 384 x 256 (96 x 128 per wavefront) when
-// buckets are large on average; the (expert, row tile) list comes from the
-// device-side plan, so no bucket size ever reaches the host.  Workgroup ids are
-// dealt round-robin to the 8 XCDs by the hardware; tile ids are assigned so
-// that every XCD works on a contiguous range ordered expert -> column tile ->
-// row tile: workgroups that share an L2 share weight panels and activation rows.
-// Wavefronts whose 64 rows lie entirely past the end of a ragged bucket skip the
-// matrix instructions (and leave their SIMD to the other wavefront).
+// expert, or 384 x 256 when buckets are large on average; the (expert, row
+// tile) list comes from the device-side plan, so no bucket size ever reaches
+// the host.  Workgroup ids are dealt round-robin to the 8 XCDs by the hardware;
+// tile ids are assigned so that every XCD works on a contiguous range ordered
+// expert -> column tile -> row tile: workgroups that share an L2 share weight
+// panels and activation rows.  Within a tile the rows are dealt to the four
+// wavefront rows in blocks of 32, and a wavefront skips the blocks that lie
+// past the end of a ragged bucket: such a tile costs ceil(rows / 128) blocks
+// per wavefront, every SIMD staying equally loaded.
 //
-// Weights are pre-packed (moe_pack_weights) in MFMA fragment order.  The packed
+// Matrix instruction.  v_mfma_f32_16x16x32_bf16: with both operands coming from
+// registers it accumulates 32 k per pass over a 16 x 16 accumulator, half the
+// accumulator traffic per flop of the 32x32x16 form; under the chip's power
+// limit it sustains about 10 % more flops (measured with random operands) and
+// this kernel gained 4-7 % from the switch.
+//
+// Weights are pre-packed (moe_pack_weights) in fragment order.  The packed
 // matrix is cut into blocks of 256 columns x 64 reduction steps = 32 KB, stored
 // column tile after column tile, k tile after k tile, so the 32 KB a workgroup
-// needs per step are contiguous.  A block holds 8 panels (32 columns) x 4
-// k-blocks (16 steps) of 1 KB, in which lane l of a wavefront owns the 8
-// consecutive k of column l % 32 that start at k = 8 * (l / 32): exactly the B
-// operand of v_mfma_f32_32x32x16_bf16.  For the up projection the panels of W1
-// and W3 alternate, so both factors of the SwiGLU product sit in the same lane
-// and accumulator index.  Activations stay row-major; their LDS tile is
-// [256 rows][64 k] with the eight 16-byte slots of a row XOR-swizzled by
+// needs per step are contiguous.  A block holds 16 panels (16 columns) x 2
+// k-blocks (32 steps) of 1 KB, in which lane l of a wavefront owns the 8
+// consecutive k of column l % 16 that start at k = 8 * (l / 16): exactly the B
+// operand of the instruction.  For the up projection the panels of W1 and W3
+// alternate, so both factors of the SwiGLU product sit in the same lane and
+// accumulator index.  Activations stay row-major; their LDS tile is
+// [rows][64 k] with the eight 16-byte slots of a row XOR-swizzled by
 // (row >> 1) & 7, conflict-free for the fills and for the fragment reads.
 //
 // Data movement.  global_load_lds_dwordx4 copies 16 bytes per lane from memory
 // straight into LDS (destination = M0 + 16 * lane, one wavefront instruction
 // fills 1 KB), so a tile needs no staging registers and no LDS store
 // instructions; the swizzle is applied by choosing which global chunk each lane
-// fetches.  Two LDS stages of 64 KB: the loads of k tile kt+1 are in flight
-// while tile kt is multiplied, and one barrier per k tile both publishes tile
-// kt and retires the stage that tile kt+1 overwrites.  The loads are issued
-// from inline assembly: the compiler then does not treat them as LDS writes
-// that every later LDS read must wait for, and the wait is explicit
-// (s_waitcnt vmcnt(0) before the barrier).
+// fetches.  Two LDS stages: the loads of k tile kt+1 are in flight while tile kt
+// is multiplied, and one barrier per k tile both publishes tile kt and retires
+// the stage that tile kt+1 overwrites.  The loads are issued from inline
+// assembly: the compiler then does not treat them as LDS writes that every
+// later LDS read must wait for, and the wait is explicit (s_waitcnt vmcnt(0)
+// before the barrier).  They are spread between the matrix instructions, and
+// the LDS fragment reads run one column ahead of the matrix instructions.
 //
 // Tail balancing (down projection).  When the last round of tiles on an XCD
 // would occupy at most half of its compute units, each of those tiles is split
@@ -52,7 +60,6 @@
 namespace moe {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
@@ -60,10 +67,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int BN = 256, BK = 64;                // tile width and k depth of one LDS stage
 constexpr int WM = 4, WN = 2, NW = WM * WN;     // wavefront grid
 constexpr int WTN = BN / WN;                    // 128 columns per wavefront
-constexpr int FN = WTN / 32;                    // 4 column fragments of 32
+constexpr int FN = WTN / 16;                    // 8 column fragments of 16
 constexpr int NS = 2;                           // LDS stages
-constexpr int kDmaEvery = 2;                    // matrix instructions between two direct-to-LDS loads of the next k tile
-constexpr int KB = BK / 16;                     // k-blocks per stage
+constexpr int kDmaEvery = 4;                    // matrix instructions between two direct-to-LDS loads of the next k tile
+constexpr int KB = BK / 32;                     // k steps of one matrix instruction per stage
 constexpr int B_CHUNKS = BN / 8;                // 1 KB pieces of the weight tile per stage
 constexpr int B_PER_WAVE = B_CHUNKS / NW;
 constexpr int kThreads = NW * 64;
@@ -73,7 +80,7 @@ template <int FM> struct Tile {
     static constexpr int A_CHUNKS = BM / 8, A_PER_WAVE = A_CHUNKS / NW;
     static constexpr size_t kPartialFloats = (size_t)BM * BN;
 };
-constexpr int kPanelCols = 32;
+constexpr int kPanelCols = 16;
 constexpr int kXcds = 8;
 constexpr int kMaxSplit = 8;
 constexpr int kMinSplitKT = 16;                 // a k part is at least this many k tiles
@@ -91,7 +98,7 @@ constexpr int kMaxCusPerXcd = 48;
 size_t ffn_bf16_scratch_bytes() { return (size_t)kXcds * kMaxCusPerXcd * kMaxPartialFloats * sizeof(float); }
 
 // One thread per 16-byte unit of the packed buffer.  Unit index within one matrix of one expert:
-// (((nt * KT + kt) * 8 + panel) * 4 + kb) * 64 + lane.
+// (((nt * KT + kt) * 16 + panel) * 2 + kb) * 64 + lane.
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restrict__ w1, const uint16_t* __restrict__ w3,
                                                         const uint16_t* __restrict__ w2, int d, int f,
                                                         long long units13, long long units2, long long total,
@@ -106,21 +113,21 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t* __restri
     const int K = up ? d : f, ncols = up ? f : d;
     const int KT = K / BK;
     const int lane = (int)(r & 63);
-    const int kb = (int)((r >> 6) & 3);
-    const int p = (int)((r >> 8) & 7);
+    const int kb = (int)((r >> 6) & 1);
+    const int p = (int)((r >> 7) & 15);
     const long long tile = r >> 11;                 // nt * KT + kt
     const int kt = (int)(tile % KT);
-    const long long panel = (tile / KT) * 8 + p;    // 32-column panel of the (interleaved) matrix
+    const long long panel = (tile / KT) * 16 + p;   // 16-column panel of the (interleaved) matrix
     const uint16_t* src;
     int col;
     if (up) {
-        col = (int)(panel / 2) * kPanelCols + lane % 32;
+        col = (int)(panel / 2) * kPanelCols + lane % 16;
         src = ((panel & 1) ? w3 : w1) + (size_t)e * d * f;
     } else {
-        col = (int)panel * kPanelCols + lane % 32;
+        col = (int)panel * kPanelCols + lane % 16;
         src = w2 + (size_t)e * d * f;
     }
-    const int k0 = kt * BK + kb * 16 + 8 * (lane / 32);
+    const int k0 = kt * BK + kb * 32 + 8 * (lane / 16);
     uint16_t v[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] = (col < ncols) ? src[(size_t)(k0 + i) * ncols + col] : (uint16_t)0;
@@ -206,11 +213,11 @@ __device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
-// Rows of a tile are dealt to the four wavefront rows in blocks of 32: fragment a of wavefront row m
-// covers tile rows 32 * (4a + m) .. +31.  A ragged tile of r rows then keeps every SIMD equally busy
-// and costs ceil(r / 128) fragment rows of matrix work instead of the whole tile.
-__device__ __forceinline__ int frag_row(int a, int wave_m) { return (a * WM + wave_m) * 32; }
-__device__ __forceinline__ int active_frags(int rows, int wave_m, int fm) {
+// Rows of a tile are dealt to the four wavefront rows in blocks of 32 (two 16-row fragments): block j of
+// wavefront row m covers tile rows 32 * (4j + m) .. +31.  A ragged tile of r rows then keeps every SIMD
+// equally busy and costs ceil(r / 128) blocks of matrix work per wavefront instead of the whole tile.
+__device__ __forceinline__ int block_row(int j, int wave_m) { return (j * WM + wave_m) * 32; }
+__device__ __forceinline__ int active_blocks(int rows, int wave_m, int fm) {
     const int n = (rows - wave_m * 32 + 32 * WM - 1) / (32 * WM);
     return n < 0 ? 0 : (n > fm ? fm : n);
 }
@@ -233,51 +240,64 @@ struct Loader {
     }
 };
 
-// One k tile of matrix instructions for a wavefront with NF active fragment rows.  With `load`, the
-// pieces of the next k tile are issued one at a time between groups of kDmaEvery matrix instructions:
-// the memory pipeline takes 16 cycles per 1 KB piece, and a wavefront that issues its pieces back to
-// back sits in the issue stage for that long while its matrix instructions wait behind them.  Pieces
-// that find no slot (few active fragments) go first.
+// One k tile of matrix instructions for a wavefront with NF active 32-row blocks (2 NF fragment rows
+// of v_mfma_f32_16x16x32_bf16).  With `load`, the pieces of the next k tile are issued one at a time
+// between groups of kDmaEvery matrix instructions: the memory pipeline takes 16 cycles per 1 KB piece,
+// and a wavefront that issues its pieces back to back sits in the issue stage for that long while its
+// matrix instructions wait behind them.  Pieces that find no slot (few active blocks) go first.
+//
+// Fragments are streamed: the weight fragment of the next column is read while the current column
+// multiplies, and each activation fragment of the next 32 k is read into place right after its last
+// use, so that a matrix instruction rarely waits for LDS.  The schedule is pinned.
 template <int FM, int NF>
-__device__ __forceinline__ void ktile(f32x16 (&acc)[FM][FN], const uint16_t* As, const Loader<FM>& ld, int kt, int stage,
+__device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* As, const Loader<FM>& ld, int kt, int stage,
                                       bool load, int wave_m, int wave_n, int lane) {
-    constexpr int BM = Tile<FM>::BM, N_DMA = Loader<FM>::N_DMA;
-    constexpr int SLOTS = KB * NF * FN / kDmaEvery;
+    constexpr int BM = Tile<FM>::BM, N_DMA = Loader<FM>::N_DMA, NR = 2 * NF;
+    constexpr int SLOTS = KB * NR * FN / kDmaEvery;
     constexpr int UPFRONT = N_DMA > SLOTS ? N_DMA - SLOTS : 0;
     const uint16_t* Bs = As + BM * BK;
     if (UPFRONT > 0 && load) {
 #pragma unroll
         for (int j = 0; j < UPFRONT; ++j) ld.issue(j, kt + 1, stage ^ 1);
     }
+    // A operand: lane l holds row l % 16 and the 8 consecutive k that start at 8 * (l / 16)
+    auto read_a = [&](int a, int ks) {
+        const int r = block_row(a >> 1, wave_m) + (a & 1) * 16 + (lane & 15);
+        return *reinterpret_cast<const bf16x8*>(As + r * BK + swz(r, ks * 4 + (lane >> 4)) * 8);
+    };
+    auto read_b = [&](int b, int ks) {
+        return *reinterpret_cast<const bf16x8*>(Bs + ((wave_n * FN + b) * KB + ks) * 512 + lane * 8);
+    };
+    bf16x8 af[NR], bq[2];
+#pragma unroll
+    for (int a = 0; a < NR; ++a) af[a] = read_a(a, 0);
+    bq[0] = read_b(0, 0);
 #pragma unroll
     for (int ks = 0; ks < KB; ++ks) {
-        bf16x8 af[NF], bfr[FN];
 #pragma unroll
-        for (int a = 0; a < NF; ++a) {
-            const int r = frag_row(a, wave_m) + (lane & 31);
-            af[a] = *reinterpret_cast<const bf16x8*>(As + r * BK + swz(r, ks * 2 + (lane >> 5)) * 8);
-        }
+        for (int b = 0; b < FN; ++b) {
+            const int c = ks * FN + b;
+            if (b + 1 < FN) bq[(c + 1) & 1] = read_b(b + 1, ks);
+            else if (ks + 1 < KB) bq[(c + 1) & 1] = read_b(0, ks + 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int b = 0; b < FN; ++b)
-            bfr[b] = *reinterpret_cast<const bf16x8*>(Bs + ((wave_n * FN + b) * KB + ks) * 512 + lane * 8);
-#pragma unroll
-        for (int a = 0; a < NF; ++a)
-#pragma unroll
-            for (int b = 0; b < FN; ++b) {
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
-                const int m = (ks * NF + a) * FN + b;
+            for (int a = 0; a < NR; ++a) {
+                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[a], bq[c & 1], acc[a][b], 0, 0, 0);
+                if (b == FN - 1 && ks + 1 < KB) af[a] = read_a(a, ks + 1);
+                const int m = c * NR + a;
+                __builtin_amdgcn_sched_barrier(0);
                 if (m % kDmaEvery == kDmaEvery - 1 && UPFRONT + m / kDmaEvery < N_DMA) {
-                    __builtin_amdgcn_sched_barrier(0);
                     if (load) ld.issue(UPFRONT + m / kDmaEvery, kt + 1, stage ^ 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+        }
     }
 }
 
-// the k loop of a wavefront with NF active fragment rows (NF = 0: it only fetches its share of the tiles)
+// the k loop of a wavefront with NF active 32-row blocks (NF = 0: it only fetches its share of the tiles)
 template <int FM, int NF>
-__device__ __forceinline__ void kloop(f32x16 (&acc)[FM][FN], const uint16_t* smem, const Loader<FM>& ld, const WorkItem& w,
+__device__ __forceinline__ void kloop(f32x4 (&acc)[2 * FM][FN], const uint16_t* smem, const Loader<FM>& ld, const WorkItem& w,
                                       int wave_m, int wave_n, int lane) {
     constexpr int STAGE = Tile<FM>::STAGE, N_DMA = Loader<FM>::N_DMA;
     int stage = 0;
@@ -297,7 +317,7 @@ __device__ __forceinline__ void kloop(f32x16 (&acc)[FM][FN], const uint16_t* sme
 
 // acc += A[row0 .. row0+rows, k tiles kt0..kt1) * B(tile), everything through LDS
 template <int FM>
-__device__ __forceinline__ void mainloop(f32x16 (&acc)[FM][FN], uint16_t* smem, const uint16_t* __restrict__ A,
+__device__ __forceinline__ void mainloop(f32x4 (&acc)[2 * FM][FN], uint16_t* smem, const uint16_t* __restrict__ A,
                                          const uint16_t* __restrict__ Bbase, int K, const WorkItem& w, int wave, int lane,
                                          int nfrag) {
     constexpr int A_PER_WAVE = Tile<FM>::A_PER_WAVE, N_DMA = Loader<FM>::N_DMA;
@@ -318,7 +338,7 @@ __device__ __forceinline__ void mainloop(f32x16 (&acc)[FM][FN], uint16_t* smem, 
 
 #pragma unroll
     for (int j = 0; j < N_DMA; ++j) ld.issue(j, w.kt0, 0);
-    // one copy of the loop per number of active fragment rows: the accumulators of the others stay zero
+    // one copy of the loop per number of active blocks: the accumulators of the others stay zero
     if (nfrag == FM) kloop<FM, FM>(acc, smem, ld, w, wave_m, wave_n, lane);
     else if (FM >= 2 && nfrag == FM - 1) kloop<FM, (FM >= 2 ? FM - 1 : 0)>(acc, smem, ld, w, wave_m, wave_n, lane);
     else if (FM >= 3 && nfrag == FM - 2) kloop<FM, (FM >= 3 ? FM - 2 : 0)>(acc, smem, ld, w, wave_m, wave_n, lane);
@@ -326,9 +346,9 @@ __device__ __forceinline__ void mainloop(f32x16 (&acc)[FM][FN], uint16_t* smem, 
 }
 
 // accumulators -> bf16 -> per-wavefront LDS staging tile (32 rows at a time) -> 16-byte stores of
-// whole lines.  accumulator v of a 32x32 fragment: row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+// whole lines.  accumulator v of a 16x16 fragment: row 4 * (lane / 16) + v, column lane % 16
 template <bool UP, int FM>
-__device__ __forceinline__ void epilogue(const f32x16 (&acc)[FM][FN], uint16_t* smem, uint16_t* __restrict__ C, int ldc,
+__device__ __forceinline__ void epilogue(const f32x4 (&acc)[2 * FM][FN], uint16_t* smem, uint16_t* __restrict__ C, int ldc,
                                          const WorkItem& w, int wave, int lane, int nfrag) {
     constexpr int OUTC = UP ? WTN / 2 : WTN;          // output columns of this wavefront
     constexpr int RS = OUTC + 8;                      // staging row stride (elements); the pad staggers the banks
@@ -338,32 +358,36 @@ __device__ __forceinline__ void epilogue(const f32x16 (&acc)[FM][FN], uint16_t* 
     uint16_t* stg = smem + wave * (32 * RS);
     const int col = (UP ? w.nt * (BN / 2) : w.nt * BN) + wave_n * OUTC + (lane % CPR) * 8;
 #pragma unroll
-    for (int a = 0; a < FM; ++a) {
-        if (a < nfrag) {
+    for (int j = 0; j < FM; ++j) {
+        if (j < nfrag) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            if (UP) {
+            for (int h = 0; h < 2; ++h) {
+                const int a = 2 * j + h;
 #pragma unroll
-                for (int b = 0; b < FN; b += 2) {
-                    const float u = acc[a][b][v], g = acc[a][b + 1][v];
-                    const float h = u / (1.0f + __expf(-u)) * g;
-                    stg[r * RS + (b >> 1) * 32 + (lane & 31)] = __builtin_bit_cast(uint16_t, (__bf16)h);
+                for (int v = 0; v < 4; ++v) {
+                    const int r = h * 16 + 4 * (lane >> 4) + v;
+                    if (UP) {
+#pragma unroll
+                        for (int b = 0; b < FN; b += 2) {
+                            const float u = acc[a][b][v], g = acc[a][b + 1][v];
+                            const float hv = u / (1.0f + __expf(-u)) * g;
+                            stg[r * RS + (b >> 1) * 16 + (lane & 15)] = __builtin_bit_cast(uint16_t, (__bf16)hv);
+                        }
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < FN; ++b)
+                            stg[r * RS + b * 16 + (lane & 15)] = __builtin_bit_cast(uint16_t, (__bf16)acc[a][b][v]);
+                    }
                 }
-            } else {
-#pragma unroll
-                for (int b = 0; b < FN; ++b)
-                    stg[r * RS + b * 32 + (lane & 31)] = __builtin_bit_cast(uint16_t, (__bf16)acc[a][b][v]);
             }
-        }
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int r = it * RPI + lane / CPR;
-            const int gr = frag_row(a, wave_m) + r;
-            if (gr < w.rows && col < ldc)
-                *reinterpret_cast<u32x4*>(C + (size_t)(w.row0 + gr) * ldc + col) =
-                    *reinterpret_cast<const u32x4*>(stg + r * RS + (lane % CPR) * 8);
-        }
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int r = it * RPI + lane / CPR;
+                const int gr = block_row(j, wave_m) + r;
+                if (gr < w.rows && col < ldc)
+                    *reinterpret_cast<u32x4*>(C + (size_t)(w.row0 + gr) * ldc + col) =
+                        *reinterpret_cast<const u32x4*>(stg + r * RS + (lane % CPR) * 8);
+            }
         }
     }
 }
@@ -404,33 +428,27 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nfrag = active_frags(w.rows, wave / WN, FM);    // fragment rows of this wavefront that hold rows of the bucket
+    const int nfrag = active_blocks(w.rows, wave / WN, FM);   // 32-row blocks of this wavefront that hold rows of the bucket
     const uint16_t* Bbase = Wp + (size_t)w.expert * expert_stride + (size_t)w.nt * ((size_t)K * BN);
 
-    f32x16 acc[FM][FN];
+    f32x4 acc[2 * FM][FN];
 #pragma unroll
-    for (int a = 0; a < FM; ++a)
+    for (int a = 0; a < 2 * FM; ++a)
 #pragma unroll
         for (int b = 0; b < FN; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+            for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
 
     mainloop<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag);
 
     if (SPLIT && w.partial >= 0) {
         if (nfrag > 0) {
-            // 16 bytes per lane and store: [fragment][quad of accumulators][thread]; fragments past the
-            // bucket's end hold zeros
+            // 16 bytes per lane and store: [fragment][thread]; fragments past the bucket's end hold zeros
             f32x4* dst = reinterpret_cast<f32x4*>(partials + (size_t)w.partial * Tile<FM>::kPartialFloats) + tid;
 #pragma unroll
-            for (int a = 0; a < FM; ++a)
+            for (int a = 0; a < 2 * FM; ++a)
 #pragma unroll
-                for (int b = 0; b < FN; ++b)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        f32x4 t = {acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
-                        dst[(size_t)((a * FN + b) * 4 + q) * kThreads] = t;
-                    }
+                for (int b = 0; b < FN; ++b) dst[(size_t)(a * FN + b) * kThreads] = acc[a][b];
         }
         return;
     }
@@ -455,28 +473,25 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
     locate_tile(plan, prefix, NT, sh.t_begin + sh.full + q, BM, w);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nfrag = active_frags(w.rows, wave / WN, FM);
+    const int nfrag = active_blocks(w.rows, wave / WN, FM);
     if (nfrag == 0) return;
-    f32x16 acc[FM][FN];
+    f32x4 acc[2 * FM][FN];
 #pragma unroll
-    for (int a = 0; a < FM; ++a)
+    for (int a = 0; a < 2 * FM; ++a)
 #pragma unroll
         for (int b = 0; b < FN; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+            for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
     for (int part = 0; part < sh.split; ++part) {
         const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * cus_per_xcd + q * sh.split + part) * Tile<FM>::kPartialFloats) + tid;
 #pragma unroll
-        for (int a = 0; a < FM; ++a) {
+        for (int a = 0; a < 2 * FM; ++a) {
 #pragma unroll
-            for (int b = 0; b < FN; ++b)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const f32x4 t = src[(size_t)((a * FN + b) * 4 + g) * kThreads];
-                    acc[a][b][4 * g] += t[0]; acc[a][b][4 * g + 1] += t[1];
-                    acc[a][b][4 * g + 2] += t[2]; acc[a][b][4 * g + 3] += t[3];
-                }
-            __builtin_amdgcn_sched_barrier(0);               // one fragment row of loads in flight at a time
+            for (int b = 0; b < FN; ++b) {
+                const f32x4 t = src[(size_t)(a * FN + b) * kThreads];
+                acc[a][b][0] += t[0]; acc[a][b][1] += t[1]; acc[a][b][2] += t[2]; acc[a][b][3] += t[3];
+            }
+            if (a & 1) __builtin_amdgcn_sched_barrier(0);    // one block of loads in flight at a time
         }
     }
     epilogue<false, FM>(acc, smem, C, ldc, w, wave, lane, nfrag);
