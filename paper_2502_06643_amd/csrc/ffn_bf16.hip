@@ -370,7 +370,7 @@ __device__ __forceinline__ void epilogue(const f32x4 (&acc)[2 * FM][FN], uint16_
 #pragma unroll
                         for (int b = 0; b < FN; b += 2) {
                             const float u = acc[a][b][v], g = acc[a][b + 1][v];
-                            const float hv = u / (1.0f + __expf(-u)) * g;
+                            const float hv = u * __builtin_amdgcn_rcpf(1.0f + __expf(-u)) * g;   // silu(u) * g; rcp is good to 1 ulp, the result is rounded to bf16
                             stg[r * RS + (b >> 1) * 16 + (lane & 15)] = __builtin_bit_cast(uint16_t, (__bf16)hv);
                         }
                     } else {
