@@ -269,9 +269,12 @@ __device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* 
         return *reinterpret_cast<const bf16x8*>(Bs + ((wave_n * FN + b) * KB + ks) * 512 + lane * 8);
     };
     bf16x8 af[NR], bq[2];
+    bq[0] = read_b(0, 0);                                    // the first matrix instruction needs only bq[0] and af[0]
 #pragma unroll
-    for (int a = 0; a < NR; ++a) af[a] = read_a(a, 0);
-    bq[0] = read_b(0, 0);
+    for (int a = 0; a < NR; ++a) {
+        af[a] = read_a(a, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 #pragma unroll
     for (int ks = 0; ks < KB; ++ks) {
 #pragma unroll
