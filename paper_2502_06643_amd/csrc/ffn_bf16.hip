@@ -10,8 +10,8 @@
 // tile) list comes from the device-side plan, so no bucket size ever reaches
 // the host.  Workgroup ids are dealt round-robin to the 8 XCDs by the hardware;
 // tile ids are assigned so that every XCD works on a contiguous range ordered
-// expert -> column tile -> row tile: workgroups that share an L2 share weight
-// panels and activation rows.  Within a tile the rows are dealt to the four
+// expert -> chunk of 4 row tiles -> column tile -> row tile: workgroups that
+// share an L2 share weight panels and activation rows.  Within a tile the rows are dealt to the four
 // wavefront rows in blocks of 32, and a wavefront skips the blocks that lie
 // past the end of a ragged bucket: such a tile costs ceil(rows / 128) blocks
 // per wavefront, every SIMD staying equally loaded.
@@ -189,15 +189,29 @@ __device__ __forceinline__ XcdShare xcd_share(long long total_tiles, int x, int 
     return s;
 }
 
+// Tile order inside one expert: row tiles are taken in chunks of `row_chunk`, and within a chunk the
+// column tile advances before the chunk does, so the ~32 tiles that run together on an XCD form a
+// row_chunk x (32 / row_chunk) block that streams row_chunk activation panels and 32 / row_chunk
+// weight panels through that XCD's L2 (a large expert would otherwise run as a 32 x 1 strip that
+// re-reads its activations once per column tile).  Every chunk re-reads the expert's weights, which
+// come from DRAM, while re-read activations come from the Infinity Cache as long as they fit there:
+// chunks of 8 row tiles then, of 4 (the split that moves the fewest bytes) for larger batches.
+constexpr size_t kActivationsFitCache = (size_t)128 << 20;
+static inline int row_chunk_for(size_t activation_bytes) { return activation_bytes <= kActivationsFitCache ? 8 : 4; }
+
 __device__ __forceinline__ void locate_tile(const int32_t* __restrict__ plan, const int32_t* __restrict__ prefix, int NT,
-                                            long long tile, int BM, WorkItem& w) {
+                                            long long tile, int BM, int row_chunk, WorkItem& w) {
     const int n_exp = plan[0];
     int i = 0;
     while (i + 1 < n_exp && (long long)prefix[i + 1] * NT <= tile) ++i;
     const int mt_e = prefix[i + 1] - prefix[i];
     const int rem = (int)(tile - (long long)prefix[i] * NT);
-    w.nt = rem / mt_e;
-    const int mt = rem - w.nt * mt_e;
+    const int per_chunk = row_chunk * NT;
+    const int q = rem / per_chunk;                       // chunk of row tiles
+    const int in_chunk = rem - q * per_chunk;
+    const int rows_here = min(row_chunk, mt_e - q * row_chunk);
+    w.nt = in_chunk / rows_here;
+    const int mt = q * row_chunk + (in_chunk - w.nt * rows_here);
     w.expert = plan[kPlanExpert + i];
     w.row0 = plan[kPlanStart + i] + mt * BM;
     w.rows = min(BM, plan[kPlanCount + i] - mt * BM);
@@ -407,7 +421,7 @@ template <bool UP, bool SPLIT, int FM>
 __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ Wp,
                                                             size_t expert_stride, int K, int npad, uint16_t* __restrict__ C,
                                                             int ldc, const int32_t* __restrict__ plan, float* __restrict__ partials,
-                                                            int cus_per_xcd) {
+                                                            int cus_per_xcd, int row_chunk) {
     constexpr int BM = Tile<FM>::BM;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int32_t* prefix = plan + (UP ? kPlanTiles0 : kPlanTiles1);
@@ -418,12 +432,12 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
     if (slot >= sh.full + sh.tail * sh.split) return;
     WorkItem w;
     if (slot < sh.full) {
-        locate_tile(plan, prefix, NT, sh.t_begin + slot, BM, w);
+        locate_tile(plan, prefix, NT, sh.t_begin + slot, BM, row_chunk, w);
         w.kt0 = 0; w.kt1 = KT; w.partial = -1;
     } else {
         const int j = slot - sh.full;
         const int part = j % sh.split;
-        locate_tile(plan, prefix, NT, sh.t_begin + sh.full + j / sh.split, BM, w);
+        locate_tile(plan, prefix, NT, sh.t_begin + sh.full + j / sh.split, BM, row_chunk, w);
         w.kt0 = (int)((long long)part * KT / sh.split);
         w.kt1 = (int)((long long)(part + 1) * KT / sh.split);
         w.partial = x * cus_per_xcd + j;
@@ -463,7 +477,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
 template <int FM>
 __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npad, uint16_t* __restrict__ C, int ldc,
                                                                   const int32_t* __restrict__ plan,
-                                                                  const float* __restrict__ partials, int cus_per_xcd) {
+                                                                  const float* __restrict__ partials, int cus_per_xcd, int row_chunk) {
     constexpr int BM = Tile<FM>::BM;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int32_t* prefix = plan + kPlanTiles1;
@@ -473,7 +487,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
     const XcdShare sh = xcd_share(total, x, KT, cus_per_xcd, true);
     if (q >= sh.tail) return;
     WorkItem w;
-    locate_tile(plan, prefix, NT, sh.t_begin + sh.full + q, BM, w);
+    locate_tile(plan, prefix, NT, sh.t_begin + sh.full + q, BM, row_chunk, w);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nfrag = active_blocks(w.rows, wave / WN, FM);
@@ -536,6 +550,7 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
     rc = launch_ffn_plan(counts, starts, placement, local_gpu, E, N, BMU, BMD, plan, s);
     if (rc != MOE_OK) return rc;
     const int cpx = cus_per_xcd();
+    const int chunk_up = row_chunk_for((size_t)N * d * 2), chunk_down = row_chunk_for((size_t)N * f * 2);
     const size_t s13 = npad13(f) * d, s2 = npad2(d) * f, stride = s13 + s2;
     const uint16_t* Wp = (const uint16_t*)packed;
     // partial tiles live behind H in the workspace
@@ -550,7 +565,7 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
         if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
         LaunchTimer timer(MOE_K_FFN_UP, s);
         hipLaunchKernelGGL((ffn_bf16_kernel<true, false, FMU>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<true, FMU>()), s,
-                           (const uint16_t*)a, Wp, stride, d, (int)npad13(f), (uint16_t*)H, f, plan, partials, cpx);
+                           (const uint16_t*)a, Wp, stride, d, (int)npad13(f), (uint16_t*)H, f, plan, partials, cpx, chunk_up);
         if ((rc = check_launch("moe_expert_ffn_grouped up launch")) != MOE_OK) return rc;
     }
     {
@@ -559,14 +574,14 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
         LaunchTimer timer(MOE_K_FFN_DOWN, s);
         if (split_down) {
             hipLaunchKernelGGL((ffn_bf16_kernel<false, true, FMD>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FMD>()), s,
-                               (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx);
+                               (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
             if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
             hipLaunchKernelGGL(ffn_bf16_fixup_kernel<FMD>, dim3(kXcds * (cpx / 2)), dim3(kThreads), (smem_bytes<false, FMD>()), s, f,
-                               (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx);
+                               (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
             if ((rc = check_launch("moe_expert_ffn_grouped fix-up launch")) != MOE_OK) return rc;
         } else {
             hipLaunchKernelGGL((ffn_bf16_kernel<false, false, FMD>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FMD>()), s,
-                               (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx);
+                               (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
             if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
         }
     }
