@@ -46,11 +46,12 @@
 // before the barrier).  They are spread between the matrix instructions, and
 // the LDS fragment reads run one column ahead of the matrix instructions.
 //
-// Tail balancing (down projection).  When the last round of tiles on an XCD
-// would occupy at most half of its compute units, each of those tiles is split
-// along k into s parts that run as separate workgroups and write fp32 partial
-// accumulators; a small fix-up kernel adds the parts in a fixed order and runs
-// the normal epilogue.  Results stay bitwise reproducible.
+// Tail balancing (down projection).  The tiles of the last, partly filled round
+// on an XCD are each split along k into s parts that run as separate workgroups
+// and write fp32 partial accumulators, s chosen so that the parts fill the
+// compute units in the fewest, shortest rounds; a small fix-up kernel adds the
+// parts in a fixed order and runs the normal epilogue.  Results stay bitwise
+// reproducible.
 //
 // Epilogue.  Accumulators are converted to bf16 (round to nearest even),
 // transposed through a per-wavefront LDS staging tile and written with
@@ -93,9 +94,9 @@ size_t packed_bytes_bf16(int E, int d, int f) {
     return (size_t)E * (npad13(f) * d + npad2(d) * f) * 2;
 }
 
-// fp32 partial tiles for the split tail of the down projection: one slot per compute unit
+// fp32 partial tiles for the split tail of the down projection: two slots per compute unit
 constexpr int kMaxCusPerXcd = 48;
-size_t ffn_bf16_scratch_bytes() { return (size_t)kXcds * kMaxCusPerXcd * kMaxPartialFloats * sizeof(float); }
+size_t ffn_bf16_scratch_bytes() { return (size_t)kXcds * 2 * kMaxCusPerXcd * kMaxPartialFloats * sizeof(float); }
 
 // One thread per 16-byte unit of the packed buffer.  Unit index within one matrix of one expert:
 // (((nt * KT + kt) * 16 + panel) * 2 + kb) * 64 + lane.
@@ -174,15 +175,21 @@ __device__ __forceinline__ XcdShare xcd_share(long long total_tiles, int x, int 
     s.tail = 0;
     s.split = 1;
     if (allow_split) {
+        // r tiles in the last round: cut each into sp k parts so that the r * sp parts (at most two per
+        // compute unit: that many partial tiles exist) fill the compute units in as few, short rounds as
+        // possible; taken when the tail then lasts at most three quarters of a whole round
         const int r = (int)(cnt % cus_per_xcd);
-        if (r > 0 && 2 * r <= cus_per_xcd) {
-            int sp = cus_per_xcd / r;
-            if (sp > kMaxSplit) sp = kMaxSplit;
-            while (sp > 1 && KT / sp < kMinSplitKT) --sp;
-            if (sp > 1) {
+        if (r > 0) {
+            int best = 1, best_num = 1, best_den = 1;           // tail time = best_num / best_den rounds
+            for (int sp = 2; sp <= kMaxSplit; ++sp) {
+                if (r * sp > 2 * cus_per_xcd || KT / sp < kMinSplitKT) break;
+                const int rounds = (r * sp + cus_per_xcd - 1) / cus_per_xcd;
+                if (rounds * best_den < best_num * sp) { best = sp; best_num = rounds; best_den = sp; }
+            }
+            if (best > 1 && 4 * best_num <= 3 * best_den) {
                 s.full = (int)cnt - r;
                 s.tail = r;
-                s.split = sp;
+                s.split = best;
             }
         }
     }
@@ -440,7 +447,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
         locate_tile(plan, prefix, NT, sh.t_begin + sh.full + j / sh.split, BM, row_chunk, w);
         w.kt0 = (int)((long long)part * KT / sh.split);
         w.kt1 = (int)((long long)(part + 1) * KT / sh.split);
-        w.partial = x * cus_per_xcd + j;
+        w.partial = x * 2 * cus_per_xcd + j;
     }
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -500,7 +507,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
     for (int part = 0; part < sh.split; ++part) {
-        const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * cus_per_xcd + q * sh.split + part) * Tile<FM>::kPartialFloats) + tid;
+        const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * 2 * cus_per_xcd + q * sh.split + part) * Tile<FM>::kPartialFloats) + tid;
 #pragma unroll
         for (int a = 0; a < 2 * FM; ++a) {
 #pragma unroll
@@ -558,7 +565,7 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
     auto grid_for = [&](size_t npad, int bm, bool split) {
         const long long mt_max = (N + bm - 1) / bm + (E < N ? E : N);     // sum of ceil(n_e / bm) never exceeds this
         const long long tiles = mt_max * (long long)(npad / BN);
-        return (long long)kXcds * ((tiles + kXcds - 1) / kXcds + (split ? cpx : 0));
+        return (long long)kXcds * ((tiles + kXcds - 1) / kXcds + (split ? 2 * cpx : 0));
     };
     {
         const long long grid = grid_for(npad13(f), BMU, false);
@@ -576,7 +583,7 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
             hipLaunchKernelGGL((ffn_bf16_kernel<false, true, FMD>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FMD>()), s,
                                (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
             if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
-            hipLaunchKernelGGL(ffn_bf16_fixup_kernel<FMD>, dim3(kXcds * (cpx / 2)), dim3(kThreads), (smem_bytes<false, FMD>()), s, f,
+            hipLaunchKernelGGL(ffn_bf16_fixup_kernel<FMD>, dim3(kXcds * cpx), dim3(kThreads), (smem_bytes<false, FMD>()), s, f,
                                (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
             if ((rc = check_launch("moe_expert_ffn_grouped fix-up launch")) != MOE_OK) return rc;
         } else {
