@@ -370,58 +370,63 @@ __device__ __forceinline__ void mainloop(f32x4 (&acc)[2 * FM][FN], uint16_t* sme
 }
 
 // accumulators -> bf16 -> per-wavefront LDS staging tile (32 rows at a time) -> 16-byte stores of
-// whole lines.  accumulator v of a 16x16 fragment: row 4 * (lane / 16) + v, column lane % 16
-template <bool UP, int FM>
-__device__ __forceinline__ void epilogue(const f32x4 (&acc)[2 * FM][FN], uint16_t* smem, uint16_t* __restrict__ C, int ldc,
-                                         const WorkItem& w, int wave, int lane, int nfrag) {
+// whole lines.  accumulator v of a 16x16 fragment: row 4 * (lane / 16) + v, column lane % 16.
+// One 32-row block (two fragment rows, blk[0] and blk[1]) whose first tile row is row_base:
+template <bool UP>
+__device__ __forceinline__ void epilogue_block(const f32x4 (&blk0)[FN], const f32x4 (&blk1)[FN], int row_base, uint16_t* smem,
+                                               uint16_t* __restrict__ C, int ldc, const WorkItem& w, int wave, int lane) {
     constexpr int OUTC = UP ? WTN / 2 : WTN;          // output columns of this wavefront
     constexpr int RS = OUTC + 8;                      // staging row stride (elements); the pad staggers the banks
     constexpr int CPR = OUTC / 8;                     // 16-byte chunks per row
     constexpr int RPI = 64 / CPR;                     // rows covered by one wavefront-wide 16-byte access
-    const int wave_m = wave / WN, wave_n = wave % WN;
+    const int wave_n = wave % WN;
     uint16_t* stg = smem + wave * (32 * RS);
     const int col = (UP ? w.nt * (BN / 2) : w.nt * BN) + wave_n * OUTC + (lane % CPR) * 8;
 #pragma unroll
-    for (int j = 0; j < FM; ++j) {
-        if (j < nfrag) {
+    for (int h = 0; h < 2; ++h) {
+        const f32x4 (&fr)[FN] = h ? blk1 : blk0;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int a = 2 * j + h;
+        for (int v = 0; v < 4; ++v) {
+            const int r = h * 16 + 4 * (lane >> 4) + v;
+            if (UP) {
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int r = h * 16 + 4 * (lane >> 4) + v;
-                    if (UP) {
-#pragma unroll
-                        for (int b = 0; b < FN; b += 2) {
-                            const float u = acc[a][b][v], g = acc[a][b + 1][v];
-                            const float hv = u * __builtin_amdgcn_rcpf(1.0f + __expf(-u)) * g;   // silu(u) * g; rcp is good to 1 ulp, the result is rounded to bf16
-                            stg[r * RS + (b >> 1) * 16 + (lane & 15)] = __builtin_bit_cast(uint16_t, (__bf16)hv);
-                        }
-                    } else {
-#pragma unroll
-                        for (int b = 0; b < FN; ++b)
-                            stg[r * RS + b * 16 + (lane & 15)] = __builtin_bit_cast(uint16_t, (__bf16)acc[a][b][v]);
-                    }
+                for (int b = 0; b < FN; b += 2) {
+                    const float u = fr[b][v], g = fr[b + 1][v];
+                    const float hv = u * __builtin_amdgcn_rcpf(1.0f + __expf(-u)) * g;   // silu(u) * g; rcp is good to 1 ulp, the result is rounded to bf16
+                    stg[r * RS + (b >> 1) * 16 + (lane & 15)] = __builtin_bit_cast(uint16_t, (__bf16)hv);
                 }
-            }
+            } else {
 #pragma unroll
-            for (int it = 0; it < 32 / RPI; ++it) {
-                const int r = it * RPI + lane / CPR;
-                const int gr = block_row(j, wave_m) + r;
-                if (gr < w.rows && col < ldc)
-                    *reinterpret_cast<u32x4*>(C + (size_t)(w.row0 + gr) * ldc + col) =
-                        *reinterpret_cast<const u32x4*>(stg + r * RS + (lane % CPR) * 8);
+                for (int b = 0; b < FN; ++b)
+                    stg[r * RS + b * 16 + (lane & 15)] = __builtin_bit_cast(uint16_t, (__bf16)fr[b][v]);
             }
         }
+    }
+#pragma unroll
+    for (int it = 0; it < 32 / RPI; ++it) {
+        const int r = it * RPI + lane / CPR;
+        const int gr = row_base + r;
+        if (gr < w.rows && col < ldc)
+            *reinterpret_cast<u32x4*>(C + (size_t)(w.row0 + gr) * ldc + col) =
+                *reinterpret_cast<const u32x4*>(stg + r * RS + (lane % CPR) * 8);
     }
 }
 
 template <bool UP, int FM>
+__device__ __forceinline__ void epilogue(const f32x4 (&acc)[2 * FM][FN], uint16_t* smem, uint16_t* __restrict__ C, int ldc,
+                                         const WorkItem& w, int wave, int lane, int nfrag) {
+#pragma unroll
+    for (int j = 0; j < FM; ++j)
+        if (j < nfrag) epilogue_block<UP>(acc[2 * j], acc[2 * j + 1], block_row(j, wave / WN), smem, C, ldc, w, wave, lane);
+}
+
+template <bool UP>
+constexpr int epilogue_bytes() { return NW * 32 * ((UP ? WTN / 2 : WTN) + 8) * 2; }
+
+template <bool UP, int FM>
 constexpr int smem_bytes() {
     constexpr int stage_bytes = NS * Tile<FM>::STAGE * 2;
-    constexpr int outc = UP ? WTN / 2 : WTN;
-    constexpr int epi_bytes = NW * 32 * (outc + 8) * 2;
-    return stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+    return stage_bytes > epilogue_bytes<UP>() ? stage_bytes : epilogue_bytes<UP>();
 }
 
 template <bool UP, bool SPLIT, int FM>
@@ -480,7 +485,8 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
     epilogue<UP, FM>(acc, smem, C, ldc, w, wave, lane, nfrag);
 }
 
-// adds the k parts of the split tail tiles in part order and writes the tiles
+// adds the k parts of the split tail tiles in part order and writes the tiles; a workgroup handles
+// the j-th 32-row block of every wavefront of one tile
 template <int FM>
 __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npad, uint16_t* __restrict__ C, int ldc,
                                                                   const int32_t* __restrict__ plan,
@@ -490,35 +496,32 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
     const int32_t* prefix = plan + kPlanTiles1;
     const int NT = npad / BN, KT = K / BK;
     const long long total = (long long)prefix[plan[0]] * NT;
-    const int x = blockIdx.x % kXcds, q = blockIdx.x / kXcds;
+    const int x = blockIdx.x % kXcds, q = (blockIdx.x / kXcds) / FM, j = (blockIdx.x / kXcds) % FM;
     const XcdShare sh = xcd_share(total, x, KT, cus_per_xcd, true);
     if (q >= sh.tail) return;
     WorkItem w;
     locate_tile(plan, prefix, NT, sh.t_begin + sh.full + q, BM, row_chunk, w);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nfrag = active_blocks(w.rows, wave / WN, FM);
-    if (nfrag == 0) return;
-    f32x4 acc[2 * FM][FN];
+    if (j >= active_blocks(w.rows, wave / WN, FM)) return;
+    f32x4 blk[2][FN];
 #pragma unroll
-    for (int a = 0; a < 2 * FM; ++a)
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
         for (int b = 0; b < FN; ++b)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
+            for (int v = 0; v < 4; ++v) blk[h][b][v] = 0.f;
     for (int part = 0; part < sh.split; ++part) {
         const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * 2 * cus_per_xcd + q * sh.split + part) * Tile<FM>::kPartialFloats) + tid;
 #pragma unroll
-        for (int a = 0; a < 2 * FM; ++a) {
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int b = 0; b < FN; ++b) {
-                const f32x4 t = src[(size_t)(a * FN + b) * kThreads];
-                acc[a][b][0] += t[0]; acc[a][b][1] += t[1]; acc[a][b][2] += t[2]; acc[a][b][3] += t[3];
+                const f32x4 t = src[(size_t)((2 * j + h) * FN + b) * kThreads];
+                blk[h][b][0] += t[0]; blk[h][b][1] += t[1]; blk[h][b][2] += t[2]; blk[h][b][3] += t[3];
             }
-            if (a & 1) __builtin_amdgcn_sched_barrier(0);    // one block of loads in flight at a time
-        }
     }
-    epilogue<false, FM>(acc, smem, C, ldc, w, wave, lane, nfrag);
+    epilogue_block<false>(blk[0], blk[1], block_row(j, wave / WN), smem, C, ldc, w, wave, lane);
 }
 
 static int cus_per_xcd() {
@@ -550,7 +553,7 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
         if ((rc = set_smem(&ffn_bf16_kernel<true, false, FMU>, smem_bytes<true, FMU>())) != MOE_OK) return rc;
         if ((rc = set_smem(&ffn_bf16_kernel<false, false, FMD>, smem_bytes<false, FMD>())) != MOE_OK) return rc;
         if ((rc = set_smem(&ffn_bf16_kernel<false, true, FMD>, smem_bytes<false, FMD>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_fixup_kernel<FMD>, smem_bytes<false, FMD>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_fixup_kernel<FMD>, epilogue_bytes<false>())) != MOE_OK) return rc;
         configured = true;
     }
     constexpr int BMU = Tile<FMU>::BM, BMD = Tile<FMD>::BM;
@@ -583,7 +586,7 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
             hipLaunchKernelGGL((ffn_bf16_kernel<false, true, FMD>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FMD>()), s,
                                (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
             if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
-            hipLaunchKernelGGL(ffn_bf16_fixup_kernel<FMD>, dim3(kXcds * cpx), dim3(kThreads), (smem_bytes<false, FMD>()), s, f,
+            hipLaunchKernelGGL(ffn_bf16_fixup_kernel<FMD>, dim3(kXcds * cpx * FMD), dim3(kThreads), (epilogue_bytes<false>()), s, f,
                                (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
             if ((rc = check_launch("moe_expert_ffn_grouped fix-up launch")) != MOE_OK) return rc;
         } else {
