@@ -113,7 +113,7 @@ def router_gate(x, w_g, bias, k: int):
 # --------------------------------------------------------------------------
 # a1  top-k gate
 # --------------------------------------------------------------------------
-def topk_gate(logits, k: int):
+def topk_gate(logits, k: int, norm: str = "selected"):
     """Top-k router (Section 2.1: each token goes to its k most relevant
     experts; Mixtral uses k=2).
 
@@ -123,6 +123,12 @@ def topk_gate(logits, k: int):
     k kept logits (identical to a softmax over all experts renormalised over
     the kept ones).  -0.0 and +0.0 compare equal.  Non-finite logits are
     rejected.
+
+    norm = "all" is the other common gating rule (the paper does not say which
+    one its models use beyond "top-2 router"): the weights are the softmax over
+    all E logits read at the kept experts, without renormalisation, so they sum
+    to the probability mass of the kept experts (< 1 unless k = E).  The
+    selection is the same.
 
     Returns (topk_idx int32 [T,k], topk_w float64 [T,k]).
     """
@@ -141,7 +147,12 @@ def topk_gate(logits, k: int):
     idx = order[:, :k]
     sel = np.take_along_axis(lg, idx, axis=1)
     p = np.exp(sel - sel[:, :1])
-    w = p / p.sum(axis=1, keepdims=True)
+    if norm == "selected":
+        w = p / p.sum(axis=1, keepdims=True)
+    elif norm == "all":
+        w = p / np.exp(lg - sel[:, :1]).sum(axis=1, keepdims=True)
+    else:
+        raise ValueError("norm must be 'selected' or 'all'")
     return idx.astype(np.int32), w
 
 
@@ -304,7 +315,7 @@ def combine(ffn_out, inv_perm, topk_idx, topk_w, placement, local_gpu: int):
 # --------------------------------------------------------------------------
 # a5  layer-l -> layer-(l+1) transition counts
 # --------------------------------------------------------------------------
-def transition_counts(idx_l, idx_l1, E_l: int, E_l1: int, R=None):
+def transition_counts(idx_l, idx_l1, E_l: int, E_l1: int, R=None, top1_only: bool = False):
     """Routing history table between neighbouring layers (Section 2.4,
     Section 3.1 "Token Routing Profile", ILP 2 input R_{e1,e2,l}):
 
@@ -313,12 +324,16 @@ def transition_counts(idx_l, idx_l1, E_l: int, E_l1: int, R=None):
     e1 is an expert of layer l, e2 an expert of layer l+1; with top-k routing
     every one of the k_l * k_{l+1} expert pairs of a token is counted.  R is
     int64 and is accumulated in place when given (profiling runs over many
-    batches).
+    batches).  top1_only counts one pair per token instead, its top-1 expert
+    in either layer (slot 0): the table of a top-1 reading of "tokens routed
+    between experts e1 and e2".
     """
     a = np.asarray(idx_l)
     b = np.asarray(idx_l1)
     if a.ndim != 2 or b.ndim != 2 or a.shape[0] != b.shape[0]:
         raise ValueError("idx_l [T,k_l] and idx_l1 [T,k_l1] must share T")
+    if top1_only:
+        a, b = a[:, :1], b[:, :1]
     a = _check_index_array("idx_l", a, 0, E_l)
     b = _check_index_array("idx_l1", b, 0, E_l1)
     if R is None:

@@ -155,3 +155,69 @@ def test_planted_mistakes_are_caught():
     bidx, bw = brute_gate(lg, 2)
     assert not np.array_equal(_wrong_tie_high_index(lg, 2)[0], bidx)
     assert not np.allclose(_wrong_softmax_over_all(lg, 2)[1], bw, rtol=1e-6)
+
+
+# ---- gating without renormalisation (softmax over all experts, read at the kept ones) ----
+
+def brute_gate_all(logits, k):
+    idx, _ = brute_gate(logits, k)
+    T, E = logits.shape
+    w = np.zeros((T, k))
+    for t in range(T):
+        m = max(float(v) for v in logits[t])
+        z = [math.exp(float(v) - m) for v in logits[t]]
+        s = 0.0
+        for v in z:
+            s += v
+        w[t] = [z[e] / s for e in idx[t]]
+    return idx, w
+
+
+@pytest.mark.parametrize("T,E,k", [(5, 4, 2), (17, 8, 2), (9, 64, 6), (3, 5, 5)])
+def test_all_norm_matches_brute_force(T, E, k):
+    rng = np.random.default_rng(T * 100 + E)
+    lg = rng.normal(size=(T, E)).astype(np.float32)
+    idx, w = O.topk_gate(lg, k, norm="all")
+    bi, bw = brute_gate_all(lg, k)
+    assert np.array_equal(idx, bi)
+    np.testing.assert_allclose(w, bw, rtol=1e-13, atol=0)
+
+
+def test_all_norm_textbook_example():
+    # logits = ln(1, 2, 3, 4): the softmax is (0.1, 0.2, 0.3, 0.4)
+    lg = np.log(np.array([[1.0, 2.0, 3.0, 4.0]]))
+    idx, w = O.topk_gate(lg, 2, norm="all")
+    assert idx.tolist() == [[3, 2]]
+    np.testing.assert_allclose(w, [[0.4, 0.3]], rtol=1e-14)
+    _, ws = O.topk_gate(lg, 2)                       # renormalised over the kept pair
+    np.testing.assert_allclose(ws, [[4 / 7, 3 / 7]], rtol=1e-14)
+
+
+def test_all_norm_is_selected_norm_times_kept_mass_and_same_selection():
+    rng = np.random.default_rng(11)
+    lg = rng.normal(size=(40, 16)) * 3
+    idx_a, w_a = O.topk_gate(lg, 4, norm="all")
+    idx_s, w_s = O.topk_gate(lg, 4)
+    assert np.array_equal(idx_a, idx_s)
+    full = scipy.special.softmax(lg, axis=1)
+    mass = np.take_along_axis(full, idx_a, axis=1).sum(axis=1, keepdims=True)
+    np.testing.assert_allclose(w_a, w_s * mass, rtol=1e-12)
+    np.testing.assert_allclose(w_a, np.take_along_axis(full, idx_a, axis=1), rtol=1e-12)
+    assert np.all(w_a.sum(axis=1) < 1.0)
+    # k = E: nothing is dropped, both rules give the full softmax
+    _, w_full = O.topk_gate(lg, 16, norm="all")
+    np.testing.assert_allclose(w_full.sum(axis=1), 1.0, rtol=1e-12)
+    np.testing.assert_allclose(w_full, O.topk_gate(lg, 16)[1], rtol=1e-12)
+
+
+def test_all_norm_uniform_logits_shift_invariance_and_large_magnitudes():
+    _, w = O.topk_gate(np.full((3, 8), 2.5), 2, norm="all")
+    np.testing.assert_allclose(w, 1 / 8, rtol=1e-14)
+    rng = np.random.default_rng(5)
+    lg = rng.normal(size=(10, 8))
+    np.testing.assert_allclose(O.topk_gate(lg + 1000.0, 2, norm="all")[1], O.topk_gate(lg, 2, norm="all")[1], rtol=1e-9)
+    _, w = O.topk_gate(np.array([[900.0, -900.0, 899.0, 0.0]]), 2, norm="all")
+    assert np.all(np.isfinite(w))
+    np.testing.assert_allclose(w[0, 0] / w[0, 1], math.e, rtol=1e-12)
+    with pytest.raises(ValueError):
+        O.topk_gate(lg, 2, norm="none")

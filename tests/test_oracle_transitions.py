@@ -97,3 +97,27 @@ def test_cluster_traffic_hand_example_and_conservation():
     C = O.cluster_traffic(R, rng.integers(0, 4, 8), rng.integers(0, 4, 8), 4)
     assert C.sum() == R.sum()
     assert O.max_pair_cost(np.array([[4, 6], [0, 9]]), np.array([[1.0, 2.0], [2.0, 4.5]])) == pytest.approx(4.0)
+
+
+def test_top1_only_counts_one_pair_per_token():
+    rng = np.random.default_rng(3)
+    T, E1, E2 = 200, 8, 6
+    a = np.stack([rng.permutation(E1)[:3] for _ in range(T)]).astype(np.int32)
+    b = np.stack([rng.permutation(E2)[:2] for _ in range(T)]).astype(np.int32)
+    R = O.transition_counts(a, b, E1, E2, top1_only=True)
+    # brute force on slot 0 of either layer
+    B = np.zeros((E1, E2), dtype=np.int64)
+    for t in range(T):
+        B[a[t, 0], b[t, 0]] += 1
+    assert np.array_equal(R, B)
+    assert R.sum() == T
+    assert np.array_equal(R.sum(axis=1), np.bincount(a[:, 0], minlength=E1))
+    assert np.array_equal(R.sum(axis=0), np.bincount(b[:, 0], minlength=E2))
+    # it is the all-pairs table of the first columns, and a subset of the full all-pairs table
+    assert np.array_equal(R, O.transition_counts(a[:, :1], b[:, :1], E1, E2))
+    assert np.all(R <= O.transition_counts(a, b, E1, E2))
+    # k = 1 in both layers: the two modes coincide
+    assert np.array_equal(O.transition_counts(a[:, :1], b[:, :1], E1, E2, top1_only=True), R)
+    # accumulates in place like the all-pairs mode
+    R2 = O.transition_counts(a, b, E1, E2, R=R.copy(), top1_only=True)
+    assert np.array_equal(R2, 2 * R)
