@@ -62,6 +62,15 @@ typedef enum {
 
 typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
 
+/* Gate weights: softmax over the k selected logits (the default everywhere),
+ * or softmax over all E logits read at the selected experts, not renormalised. */
+typedef enum { MOE_NORM_SOFTMAX_SELECTED = 0, MOE_NORM_SOFTMAX_ALL = 1 } moe_norm_t;
+
+/* Expert pairs a token contributes to the routing history table: all
+ * k_l * k_l1 pairs of its experts in the two layers, or only the pair of its
+ * top-1 experts (slot 0 of either index array). */
+typedef enum { MOE_PAIRS_ALL = 0, MOE_PAIRS_TOP1 = 1 } moe_pairs_t;
+
 /* Kernels that can be timed with moe_timing_begin / moe_timing_end. */
 typedef enum {
     MOE_K_GATE = 0,
@@ -100,6 +109,14 @@ const char* moe_version(void);
  * ---------------------------------------------------------------------- */
 int moe_topk_gate(const float* logits, int T, int E, int k,
                   int32_t* topk_idx, float* topk_w, void* stream);
+
+/* moe_topk_gate with the gate-weight rule spelled out (Section 2.1 fixes the
+ * top-k selection only).  MOE_NORM_SOFTMAX_SELECTED is moe_topk_gate;
+ * MOE_NORM_SOFTMAX_ALL writes topk_w[t][j] = softmax(logits[t])[topk_idx[t][j]],
+ * so a token's weights sum to the probability mass of its k experts.  The
+ * selection and everything else are the same. */
+int moe_topk_gate_norm(const float* logits, int T, int E, int k, moe_norm_t norm,
+                       int32_t* topk_idx, float* topk_w, void* stream);
 
 /* ------------------------------------------------------------------------
  * moe_router_gate - the linear router in front of the gate (Section 2.1):
@@ -243,6 +260,14 @@ int moe_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm,
 int moe_transition_counts(const int32_t* idx_l, const int32_t* idx_l1,
                           int T, int k_l, int k_l1, int E_l, int E_l1,
                           int64_t* R, void* stream);
+
+/* moe_transition_counts with the counted pairs spelled out (Section 3.1 says
+ * "tokens routed between experts e1 and e2" without fixing what a top-k token
+ * contributes).  MOE_PAIRS_ALL is moe_transition_counts; MOE_PAIRS_TOP1 adds one
+ * pair per token, (idx_l[t][0], idx_l1[t][0]).  Same arguments and errors. */
+int moe_transition_counts_pairs(const int32_t* idx_l, const int32_t* idx_l1,
+                                int T, int k_l, int k_l1, int E_l, int E_l1,
+                                moe_pairs_t pairs, int64_t* R, void* stream);
 
 /* ------------------------------------------------------------------------
  * Placement evaluators: the inputs and objective terms of the paper's two ILPs

@@ -18,14 +18,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmoetuner_hip.so")
 
 MOE_F32, MOE_BF16 = 0, 1
+MOE_NORM_SOFTMAX_SELECTED, MOE_NORM_SOFTMAX_ALL = 0, 1
+MOE_PAIRS_ALL, MOE_PAIRS_TOP1 = 0, 1
 MOE_MAX_EXPERTS, MOE_MAX_GPUS, MOE_MAX_TOPK = 256, 256, 16
 KERNEL_NAMES = ["gate", "dispatch_count", "dispatch_scan", "dispatch_rank", "dispatch_rows",
                 "ffn_plan", "ffn_up", "ffn_down", "combine", "transition", "router"]
 MOE_K_COUNT = len(KERNEL_NAMES)
 
-EXPORTS = ["moe_last_error", "moe_version", "moe_topk_gate", "moe_router_packed_bytes", "moe_pack_router", "moe_router_gate", "moe_dispatch_workspace_bytes", "moe_dispatch",
+EXPORTS = ["moe_last_error", "moe_version", "moe_topk_gate", "moe_topk_gate_norm", "moe_router_packed_bytes", "moe_pack_router", "moe_router_gate", "moe_dispatch_workspace_bytes", "moe_dispatch",
            "moe_packed_weights_bytes", "moe_pack_weights", "moe_ffn_workspace_bytes", "moe_expert_ffn_grouped",
-           "moe_combine", "moe_transition_counts", "moe_accumulate_counts", "moe_placement_loads",
+           "moe_combine", "moe_transition_counts", "moe_transition_counts_pairs", "moe_accumulate_counts", "moe_placement_loads",
            "moe_placement_traffic", "moe_timing_begin", "moe_timing_end"]
 
 
@@ -44,6 +46,7 @@ _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 _lib.moe_last_error.restype = ctypes.c_char_p
 _lib.moe_version.restype = ctypes.c_char_p
 _lib.moe_topk_gate.argtypes = [_vp, _i, _i, _i, _vp, _vp, _vp]
+_lib.moe_topk_gate_norm.argtypes = [_vp, _i, _i, _i, _i, _vp, _vp, _vp]
 _lib.moe_router_packed_bytes.argtypes = [_i, _i, _i]
 _lib.moe_router_packed_bytes.restype = _sz
 _lib.moe_pack_router.argtypes = [_vp, _i, _i, _i, _vp, _sz, _vp]
@@ -59,6 +62,7 @@ _lib.moe_ffn_workspace_bytes.restype = _sz
 _lib.moe_expert_ffn_grouped.argtypes = [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]
 _lib.moe_combine.argtypes = [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
 _lib.moe_transition_counts.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
+_lib.moe_transition_counts_pairs.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp]
 _lib.moe_accumulate_counts.argtypes = [_vp, _i, _vp, _vp]
 _lib.moe_placement_loads.argtypes = [_vp, _vp, _i, _i, _vp, _vp, _vp]
 _lib.moe_placement_traffic.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp]
@@ -108,6 +112,11 @@ def moe_last_error() -> str:
 def moe_topk_gate(logits, T, E, k, topk_idx, topk_w):
     _dev(logits, topk_idx, topk_w)
     _check(_lib.moe_topk_gate(_ptr(logits), T, E, k, _ptr(topk_idx), _ptr(topk_w), _stream()))
+
+
+def moe_topk_gate_norm(logits, T, E, k, norm, topk_idx, topk_w):
+    _dev(logits, topk_idx, topk_w)
+    _check(_lib.moe_topk_gate_norm(_ptr(logits), T, E, k, norm, _ptr(topk_idx), _ptr(topk_w), _stream()))
 
 
 def moe_router_packed_bytes(d, E, dt) -> int:
@@ -168,6 +177,11 @@ def moe_combine(ffn_out, dt, inv_perm, topk_idx, topk_w, placement, local_gpu, T
 def moe_transition_counts(idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1, R):
     _dev(idx_l, idx_l1, R)
     _check(_lib.moe_transition_counts(_ptr(idx_l), _ptr(idx_l1), T, k_l, k_l1, E_l, E_l1, _ptr(R), _stream()))
+
+
+def moe_transition_counts_pairs(idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1, pairs, R):
+    _dev(idx_l, idx_l1, R)
+    _check(_lib.moe_transition_counts_pairs(_ptr(idx_l), _ptr(idx_l1), T, k_l, k_l1, E_l, E_l1, pairs, _ptr(R), _stream()))
 
 
 def moe_accumulate_counts(expert_counts, E, P):

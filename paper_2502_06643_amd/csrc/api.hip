@@ -94,7 +94,8 @@ int moe_timing_end(double* sum_ms, int* launches) {
     return rc;
 }
 
-int moe_topk_gate(const float* logits, int T, int E, int k, int32_t* topk_idx, float* topk_w, void* stream) {
+int moe_topk_gate_norm(const float* logits, int T, int E, int k, moe_norm_t norm, int32_t* topk_idx, float* topk_w, void* stream) {
+    REQUIRE(norm == MOE_NORM_SOFTMAX_SELECTED || norm == MOE_NORM_SOFTMAX_ALL, "moe_topk_gate: unknown norm %d", (int)norm);
     REQUIRE(T >= 0, "moe_topk_gate: T=%d < 0", T);
     REQUIRE(E >= 1 && E <= MOE_MAX_EXPERTS, "moe_topk_gate: E=%d outside [1,%d]", E, MOE_MAX_EXPERTS);
     REQUIRE(k >= 1 && k <= E && k <= MOE_MAX_TOPK, "moe_topk_gate: k=%d outside [1,min(E=%d,%d)]", k, E, MOE_MAX_TOPK);
@@ -102,7 +103,11 @@ int moe_topk_gate(const float* logits, int T, int E, int k, int32_t* topk_idx, f
     if (T == 0) return MOE_OK;
     REQUIRE(logits && topk_idx && topk_w, "moe_topk_gate: NULL pointer");
     REQUIRE(aligned16(logits) && aligned16(topk_idx) && aligned16(topk_w), "moe_topk_gate: pointers must be 16-byte aligned");
-    return launch_gate(logits, T, E, k, topk_idx, topk_w, (hipStream_t)stream);
+    return launch_gate(logits, T, E, k, norm == MOE_NORM_SOFTMAX_ALL, topk_idx, topk_w, (hipStream_t)stream);
+}
+
+int moe_topk_gate(const float* logits, int T, int E, int k, int32_t* topk_idx, float* topk_w, void* stream) {
+    return moe_topk_gate_norm(logits, T, E, k, MOE_NORM_SOFTMAX_SELECTED, topk_idx, topk_w, stream);
 }
 
 static int check_router_shape(const char* who, int d, int E, moe_dtype_t dt) {
@@ -253,8 +258,9 @@ int moe_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm, co
     return launch_combine(ffn_out, dt, inv_perm, topk_idx, topk_w, placement, local_gpu, T, d, E, k, y, (hipStream_t)stream);
 }
 
-int moe_transition_counts(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_l, int k_l1, int E_l, int E_l1,
-                          int64_t* R, void* stream) {
+int moe_transition_counts_pairs(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_l, int k_l1, int E_l, int E_l1,
+                                moe_pairs_t pairs, int64_t* R, void* stream) {
+    REQUIRE(pairs == MOE_PAIRS_ALL || pairs == MOE_PAIRS_TOP1, "moe_transition_counts: unknown pair mode %d", (int)pairs);
     REQUIRE(T >= 0, "moe_transition_counts: T=%d < 0", T);
     REQUIRE(E_l >= 1 && E_l <= MOE_MAX_EXPERTS && E_l1 >= 1 && E_l1 <= MOE_MAX_EXPERTS,
             "moe_transition_counts: E_l=%d, E_l1=%d outside [1,%d]", E_l, E_l1, MOE_MAX_EXPERTS);
@@ -264,7 +270,12 @@ int moe_transition_counts(const int32_t* idx_l, const int32_t* idx_l1, int T, in
     REQUIRE(R != nullptr, "moe_transition_counts: NULL R");
     if (T == 0) return MOE_OK;
     REQUIRE(idx_l && idx_l1, "moe_transition_counts: NULL index pointer");
-    return launch_transition(idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1, R, (hipStream_t)stream);
+    return launch_transition(idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1, pairs == MOE_PAIRS_TOP1, R, (hipStream_t)stream);
+}
+
+int moe_transition_counts(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_l, int k_l1, int E_l, int E_l1,
+                          int64_t* R, void* stream) {
+    return moe_transition_counts_pairs(idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1, MOE_PAIRS_ALL, R, stream);
 }
 
 int moe_accumulate_counts(const int32_t* expert_counts, int E, int64_t* P, void* stream) {

@@ -35,7 +35,7 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int elt_bytes(moe_dtype_t dt) { return dt == MOE_BF16 ? 2 : 4; }
 
 // ---- launchers implemented in the .hip files --------------------------------
-int launch_gate(const float* logits, int T, int E, int k, int32_t* idx, float* w, hipStream_t s);
+int launch_gate(const float* logits, int T, int E, int k, bool all_norm, int32_t* idx, float* w, hipStream_t s);
 
 constexpr int kDispatchBlock = 256;
 constexpr int kDispatchItems = 4;
@@ -50,7 +50,7 @@ int launch_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm,
                    void* y, hipStream_t s);
 
 int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_l, int k_l1, int E_l,
-                      int E_l1, int64_t* R, hipStream_t s);
+                      int E_l1, bool top1_only, int64_t* R, hipStream_t s);
 
 size_t router_packed_bytes(int d, int E, moe_dtype_t dt);
 int launch_pack_router(const void* w_g, int d, int E, moe_dtype_t dt, void* packed, hipStream_t s);

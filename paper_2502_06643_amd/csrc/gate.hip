@@ -8,7 +8,10 @@
 // strict '>' (ascending index, so the lowest index wins a tie), then an
 // xor-butterfly over the L lanes on (key, index) with the same tie rule, then
 // the owner retires the winner.  k rounds give the experts in descending logit
-// order.  Weights are the softmax over the k selected logits in fp32.
+// order.  Weights are the softmax over the k selected logits in fp32, or (ALL)
+// the softmax over all E logits read at the selected experts: then every lane
+// adds exp(logit - top) over its own logits after the first round and a
+// butterfly sum over the L lanes gives the denominator.
 #include "common.h"
 
 namespace moe {
@@ -24,7 +27,7 @@ __device__ __forceinline__ float from_orderable(uint32_t o) {
     return __uint_as_float(u);
 }
 
-template <int L, int VPL, int KMAX>
+template <int L, int VPL, int KMAX, bool ALL>
 __global__ __launch_bounds__(256) void gate_kernel(const float* __restrict__ logits, int T, int E, int k,
                                                    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
     constexpr int TOK_PER_BLOCK = 256 / L;
@@ -76,6 +79,16 @@ __global__ __launch_bounds__(256) void gate_kernel(const float* __restrict__ log
                 const int oe = __shfl_xor(be, m, 64);
                 if (ok > best || (ok == best && oe < be)) { best = ok; be = oe; }
             }
+            if (ALL && j == 0) {                    // before the winner is retired: every logit still has its key
+                const float t0 = from_orderable(best);
+                float sum = 0.f;
+#pragma unroll
+                for (int i = 0; i < VPL; ++i)
+                    if (key[i] != 0u) sum += expf(from_orderable(key[i]) - t0);
+#pragma unroll
+                for (int m = 1; m < L; m <<= 1) sum += __shfl_xor(sum, m, 64);
+                denom = sum;
+            }
             const int mine = be - e0;               // in [0,VPL) only for the owner lane
 #pragma unroll
             for (int i = 0; i < VPL; ++i)
@@ -83,7 +96,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const float* __restrict__ log
             const float lj = from_orderable(best);
             if (j == 0) top = lj;
             const float p = expf(lj - top);         // exp(0) = 1 for the top-1 expert
-            denom += p;
+            if (!ALL) denom += p;
             p_sel[j] = p;
             e_sel[j] = be;
         }
@@ -103,24 +116,30 @@ __global__ __launch_bounds__(256) void gate_kernel(const float* __restrict__ log
     }
 }
 
-template <int L, int VPL>
+template <int L, int VPL, bool ALL>
 static void launch_l(const float* logits, int T, int E, int k, int32_t* idx, float* w, hipStream_t s) {
     constexpr int TOK_PER_BLOCK = 256 / L;
     const unsigned grid = (unsigned)(((long long)T + TOK_PER_BLOCK - 1) / TOK_PER_BLOCK);
-    if (k <= 2) hipLaunchKernelGGL((gate_kernel<L, VPL, 2>), dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
-    else if (k <= 8) hipLaunchKernelGGL((gate_kernel<L, VPL, 8>), dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
-    else hipLaunchKernelGGL((gate_kernel<L, VPL, MOE_MAX_TOPK>), dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
+    if (k <= 2) hipLaunchKernelGGL((gate_kernel<L, VPL, 2, ALL>), dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
+    else if (k <= 8) hipLaunchKernelGGL((gate_kernel<L, VPL, 8, ALL>), dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
+    else hipLaunchKernelGGL((gate_kernel<L, VPL, MOE_MAX_TOPK, ALL>), dim3(grid), dim3(256), 0, s, logits, T, E, k, idx, w);
 }
 
-int launch_gate(const float* logits, int T, int E, int k, int32_t* idx, float* w, hipStream_t s) {
+template <bool ALL>
+static void launch_e(const float* logits, int T, int E, int k, int32_t* idx, float* w, hipStream_t s) {
+    if (E <= 4) launch_l<1, 4, ALL>(logits, T, E, k, idx, w, s);
+    else if (E <= 8) launch_l<1, 8, ALL>(logits, T, E, k, idx, w, s);
+    else if (E <= 16) launch_l<2, 8, ALL>(logits, T, E, k, idx, w, s);
+    else if (E <= 32) launch_l<4, 8, ALL>(logits, T, E, k, idx, w, s);
+    else if (E <= 64) launch_l<4, 16, ALL>(logits, T, E, k, idx, w, s);
+    else if (E <= 128) launch_l<8, 16, ALL>(logits, T, E, k, idx, w, s);
+    else launch_l<16, 16, ALL>(logits, T, E, k, idx, w, s);
+}
+
+int launch_gate(const float* logits, int T, int E, int k, bool all_norm, int32_t* idx, float* w, hipStream_t s) {
     LaunchTimer timer(MOE_K_GATE, s);
-    if (E <= 4) launch_l<1, 4>(logits, T, E, k, idx, w, s);
-    else if (E <= 8) launch_l<1, 8>(logits, T, E, k, idx, w, s);
-    else if (E <= 16) launch_l<2, 8>(logits, T, E, k, idx, w, s);
-    else if (E <= 32) launch_l<4, 8>(logits, T, E, k, idx, w, s);
-    else if (E <= 64) launch_l<4, 16>(logits, T, E, k, idx, w, s);
-    else if (E <= 128) launch_l<8, 16>(logits, T, E, k, idx, w, s);
-    else launch_l<16, 16>(logits, T, E, k, idx, w, s);
+    if (all_norm) launch_e<true>(logits, T, E, k, idx, w, s);
+    else launch_e<false>(logits, T, E, k, idx, w, s);
     return check_launch("moe_topk_gate launch");
 }
 

@@ -168,7 +168,7 @@ int launch_router_gate(const void* x, moe_dtype_t dt, const void* packed, const 
         int rc = check_launch("moe_router_gate projection launch");
         if (rc != MOE_OK) return rc;
     }
-    return launch_gate(logits, T, E, k, idx, w, s);
+    return launch_gate(logits, T, E, k, false, idx, w, s);
 }
 
 }  // namespace moe

@@ -5,7 +5,7 @@
 // Each workgroup keeps private int32 copies of the E_l x E_l1 table in LDS
 // (as many copies as fit, up to 32, selected by lane so that lanes hitting the
 // same hot bin mostly land on different addresses), counts its tokens'
-// k_l * k_l1 expert pairs there with LDS atomics, and then adds its non-zero
+// k_l * k_l1 expert pairs (or only its top-1 pair) there with LDS atomics, and then adds its non-zero
 // bins to the int64 table in memory.  Integer adds commute, so the result is
 // exact whatever the order.  Tables too large for LDS are counted straight
 // into memory.
@@ -18,8 +18,8 @@ constexpr int kTokPerThread = 4;
 
 template <bool USE_LDS>
 __global__ __launch_bounds__(256) void transition_kernel(const int32_t* __restrict__ idx_l, const int32_t* __restrict__ idx_l1,
-                                                         int T, int k_l, int k_l1, int E_l, int E_l1, int copies,
-                                                         unsigned long long* __restrict__ R) {
+                                                         int T, int k_l, int k_l1, int use_l, int use_l1, int E_l, int E_l1,
+                                                         int copies, unsigned long long* __restrict__ R) {
     extern __shared__ int hist[];
     const int bins = E_l * E_l1;
     const int my_copy = threadIdx.x & (copies - 1);
@@ -29,10 +29,10 @@ __global__ __launch_bounds__(256) void transition_kernel(const int32_t* __restri
     }
     const long long stride = (long long)gridDim.x * 256;
     for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < T; t += stride) {
-        for (int j1 = 0; j1 < k_l; ++j1) {
+        for (int j1 = 0; j1 < use_l; ++j1) {              // the first use_l of the k_l slots (all of them, or the top-1)
             const int e1 = idx_l[t * k_l + j1];
             if ((unsigned)e1 >= (unsigned)E_l) continue;
-            for (int j2 = 0; j2 < k_l1; ++j2) {
+            for (int j2 = 0; j2 < use_l1; ++j2) {
                 const int e2 = idx_l1[t * k_l1 + j2];        // re-read per pair: it stays in L1, and no private array is needed
                 if ((unsigned)e2 >= (unsigned)E_l1) continue;
                 if (USE_LDS) atomicAdd(&hist[(e1 * E_l1 + e2) * copies + my_copy], 1);
@@ -51,7 +51,8 @@ __global__ __launch_bounds__(256) void transition_kernel(const int32_t* __restri
 }
 
 int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_l, int k_l1, int E_l, int E_l1,
-                      int64_t* R, hipStream_t s) {
+                      bool top1_only, int64_t* R, hipStream_t s) {
+    const int use_l = top1_only ? 1 : k_l, use_l1 = top1_only ? 1 : k_l1;
     const int bins = E_l * E_l1;
     long long want = ((long long)T + 256 * kTokPerThread - 1) / (256 * kTokPerThread);
     const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 512 ? 512 : want));
@@ -60,9 +61,9 @@ int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_
     LaunchTimer timer(MOE_K_TRANSITION, s);
     if (bins <= kLdsBins)
         hipLaunchKernelGGL(transition_kernel<true>, dim3(grid), dim3(256), bins * copies * sizeof(int), s, idx_l, idx_l1, T, k_l, k_l1,
-                           E_l, E_l1, copies, (unsigned long long*)R);
+                           use_l, use_l1, E_l, E_l1, copies, (unsigned long long*)R);
     else
-        hipLaunchKernelGGL(transition_kernel<false>, dim3(grid), dim3(256), 0, s, idx_l, idx_l1, T, k_l, k_l1, E_l, E_l1, 1,
+        hipLaunchKernelGGL(transition_kernel<false>, dim3(grid), dim3(256), 0, s, idx_l, idx_l1, T, k_l, k_l1, use_l, use_l1, E_l, E_l1, 1,
                            (unsigned long long*)R);
     return check_launch("moe_transition_counts launch");
 }

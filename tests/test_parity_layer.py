@@ -156,3 +156,48 @@ def test_c5_chained_layers_and_transition_counts(lib):
         x_dev = L.y.clone()
         del weights
     print("c5: fraction of tokens whose next-layer top-1 is a successor expert:", affinity)
+
+
+@pytest.mark.parametrize("tp", [2, 4])
+def test_tensor_parallel_expert_shards_full_size_sampled(lib, tp):
+    """Section 4 runs 4EP-2TP and 4EP-4TP: every expert's FFN is cut along f over tp ranks.  One rank's
+    share is the same path at f / tp (its slices of W1, W3 and W2); the all-reduce of the partial outputs
+    is not part of this build.  Mixtral shape, EP=4 map, sampled against the oracle like the other configs."""
+    cfg = synth.config("c2b")
+    cfg = cfg.with_(f=cfg.f // tp, name=f"c2b_tp{tp}")
+    x = synth.make_x(cfg)
+    lg = synth.make_logits(cfg, x)
+    weights = synth.make_expert_weights(cfg)
+    pl = synth.make_placement(cfg)
+    L = run_gpu_layer(cfg, x, lg, weights, pl, cfg.local_gpu)
+    check_sampled_layer(cfg, L, x, lg, weights, pl, cfg.local_gpu, per_expert=12)
+
+
+def test_tensor_parallel_shards_add_up_to_the_whole_expert(lib):
+    """SwiGLU is element-wise along f, so the down projections of the f-shards add up to the unsharded
+    FFN: checked on the fp32 path (1e-4), where the only difference is the order of the fp32 sums."""
+    T, d, f, E, k, tp = 300, 64, 256, 4, 2, 4
+    x = synth.normal(5, 0, (T, d), 1.0, "f32")
+    w1 = synth.normal(5, 2, (E, d, f), 1 / np.sqrt(d), "f32")
+    w3 = synth.normal(5, 3, (E, d, f), 1 / np.sqrt(d), "f32")
+    w2 = synth.normal(5, 4, (E, f, d), 1 / np.sqrt(f), "f32")
+    idx = synth.random_topk_idx(5, T, E, k)
+    pl = np.zeros(E, dtype=np.int32)
+
+    def ffn(w1s, w3s, w2s):
+        L = MoELayer(T, d, w1s.shape[2], E, k, 1, -1, "f32")
+        L.set_placement(pl)
+        L.set_weights(np.ascontiguousarray(w1s), np.ascontiguousarray(w3s), np.ascontiguousarray(w2s))
+        L.topk_idx.copy_(torch.from_numpy(idx))
+        L.dispatch(to_device(x))
+        L.ffn()
+        torch.cuda.synchronize()
+        return L.ffn_out.cpu().numpy().astype(np.float64)
+
+    whole = ffn(w1, w3, w2)
+    fs = f // tp
+    parts = sum(ffn(w1[:, :, r * fs:(r + 1) * fs], w3[:, :, r * fs:(r + 1) * fs], w2[:, r * fs:(r + 1) * fs, :]) for r in range(tp))
+    assert rel_err(parts, whole) <= TOL_F32
+    dsp = O.dispatch(x, idx, pl, 1)
+    ref = O.expert_ffn_grouped(dsp["send_buf"], w1, w3, w2, dsp["expert_counts"], dsp["expert_start"], pl, -1)
+    assert rel_err(parts, ref) <= TOL_F32
