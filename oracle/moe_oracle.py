@@ -282,6 +282,85 @@ def expert_ffn_grouped(send_buf, w1, w3, w2, expert_counts, expert_start,
     return out
 
 
+def expert_ffn_segments(recv_buf, w1, w3, w2, seg_expert, seg_counts, seg_start, positions=None):
+    """The same SwiGLU FFN over row segments: segment s is the seg_counts[s]
+    rows of recv_buf that start at seg_start[s] and belong to expert
+    seg_expert[s].  This is what a GPU computes after the first all-to-all of
+    Section 2.2 / Fig. 2b: the buffer it receives is the concatenation, source
+    GPU after source GPU, of the buckets the sources sorted by expert, so an
+    expert's rows arrive as one segment per source.  Several segments may name
+    the same expert; segments must not overlap.  Returns float64 [N,d]; rows
+    outside every segment are zero.  positions as in expert_ffn_grouped.
+    """
+    rb = np.asarray(recv_buf)
+    N, d = rb.shape
+    w1 = np.asarray(w1); w3 = np.asarray(w3); w2 = np.asarray(w2)
+    E, _, f = w1.shape
+    if w1.shape != (E, d, f) or w3.shape != (E, d, f) or w2.shape != (E, f, d):
+        raise ValueError("weights must be W1,W3 [E,d,f] and W2 [E,f,d]")
+    se = _check_index_array("seg_expert", np.asarray(seg_expert), 0, E)
+    sc = np.asarray(seg_counts).astype(np.int64)
+    ss = np.asarray(seg_start).astype(np.int64)
+    if not (se.ndim == 1 and se.shape == sc.shape == ss.shape):
+        raise ValueError("seg_expert, seg_counts, seg_start must be 1-D and of one length")
+    if np.any(sc < 0) or np.any(ss < 0) or np.any(ss + sc > N):
+        raise ValueError("segment outside the buffer")
+    covered = np.zeros(N, dtype=np.int64)
+    for s_ in range(len(se)):
+        covered[ss[s_]:ss[s_] + sc[s_]] += 1
+    if np.any(covered > 1):
+        raise ValueError("segments overlap")
+    want = None
+    if positions is not None:
+        want = np.zeros(N, dtype=bool)
+        want[np.asarray(positions, dtype=np.int64)] = True
+    out = np.zeros((N, d), dtype=np.float64)
+    for s_ in range(len(se)):
+        rows = np.arange(ss[s_], ss[s_] + sc[s_])
+        if want is not None:
+            rows = rows[want[rows]]
+        if rows.size == 0:
+            continue
+        e = se[s_]
+        a = widen(rb[rows])
+        u = a @ widen(w1[e])
+        v = a @ widen(w3[e])
+        with np.errstate(over="ignore"):
+            h = u / (1.0 + np.exp(-u)) * v
+        out[rows] = h @ widen(w2[e])
+    return out
+
+
+def exchange_to(dispatched, placement, dest: int):
+    """What GPU `dest` holds after the first all-to-all (Section 2.2): the
+    dest-buckets of every source GPU's send buffer, source after source.
+
+    dispatched: one dispatch() result per source GPU, in source order, all with
+    the same expert -> GPU map.  Returns a dict: recv_buf [N_recv,d]; seg_expert,
+    seg_counts, seg_start, seg_source (one segment per (source, expert on
+    dest) in source-major, expert-ascending order, empty segments included);
+    src_offset [G+1] = where each source's rows start in recv_buf.
+    """
+    pl = np.asarray(placement).astype(np.int64)
+    experts = [e for e in range(len(pl)) if pl[e] == dest]
+    bufs, seg_e, seg_c, seg_s, seg_src, src_off = [], [], [], [], [], [0]
+    pos = 0
+    for src, dsp in enumerate(dispatched):
+        lo = int(dsp["gpu_offsets"][dest]); n = int(dsp["gpu_counts"][dest])
+        bufs.append(np.asarray(dsp["send_buf"])[lo:lo + n])
+        for e in experts:                              # the source sorted its dest-bucket by expert
+            c = int(dsp["expert_counts"][e])
+            seg_e.append(e); seg_c.append(c); seg_s.append(pos); seg_src.append(src)
+            pos += c
+        if pos - src_off[-1] != n:
+            raise ValueError("a source's bucket for dest does not add up to its experts' counts")
+        src_off.append(pos)
+    recv = np.concatenate(bufs, axis=0) if bufs else np.zeros((0, 0))
+    return dict(recv_buf=recv, seg_expert=np.array(seg_e, dtype=np.int32), seg_counts=np.array(seg_c, dtype=np.int32),
+                seg_start=np.array(seg_s, dtype=np.int32), seg_source=np.array(seg_src, dtype=np.int32),
+                src_offset=np.array(src_off, dtype=np.int64))
+
+
 # --------------------------------------------------------------------------
 # a4  gate-weighted combine
 # --------------------------------------------------------------------------

@@ -190,3 +190,92 @@ def test_whole_layer_equals_dense_definition():
             e = r["topk_idx"][t, j]
             acc += r["topk_w"][t, j] * np.array(scalar_ffn_row(x[t], w1[e], w3[e], w2[e]))
         np.testing.assert_allclose(r["y"][t], acc, rtol=1e-12, atol=1e-13)
+
+
+# ---- receive side: the FFN over (source GPU, expert) segments and the exchange that builds them ----
+
+def ranks_problem(seed, G=4, T_rank=13, d=5, f=7, E=8, k=2):
+    rng = np.random.default_rng(seed)
+    w1 = rng.standard_normal((E, d, f)).astype(np.float32)
+    w3 = rng.standard_normal((E, d, f)).astype(np.float32)
+    w2 = rng.standard_normal((E, f, d)).astype(np.float32)
+    pl = rng.permutation(np.arange(E) % G).astype(np.int32)          # non-contiguous map, 2 experts per GPU
+    xs = [rng.standard_normal((T_rank, d)).astype(np.float32) for _ in range(G)]
+    idxs = [synth.random_topk_idx(seed * 10 + r, T_rank, E, k) for r in range(G)]
+    dsps = [O.dispatch(xs[r], idxs[r], pl, G) for r in range(G)]
+    return w1, w3, w2, pl, xs, idxs, dsps
+
+
+def test_segments_equal_the_grouped_ffn_when_segments_are_the_experts():
+    x, w1, w3, w2, idx, pl, dsp = small_problem(3)
+    E = len(pl)
+    a = O.expert_ffn_grouped(dsp["send_buf"], w1, w3, w2, dsp["expert_counts"], dsp["expert_start"], pl, -1)
+    b = O.expert_ffn_segments(dsp["send_buf"], w1, w3, w2, np.arange(E), dsp["expert_counts"], dsp["expert_start"])
+    np.testing.assert_array_equal(a, b)
+    # an expert split into two segments, listed in another order: every row still gets the same result
+    c0 = dsp["expert_counts"].astype(np.int64); s0 = dsp["expert_start"].astype(np.int64)
+    half = c0 // 2
+    se = np.concatenate([np.arange(E)[::-1], np.arange(E)])
+    sc = np.concatenate([(c0 - half)[::-1], half])
+    ss = np.concatenate([(s0 + half)[::-1], s0])
+    np.testing.assert_allclose(O.expert_ffn_segments(dsp["send_buf"], w1, w3, w2, se, sc, ss), a, rtol=1e-13, atol=1e-13)
+
+
+def test_segments_match_scalar_loops_and_reject_bad_segments():
+    w1, w3, w2, pl, xs, idxs, dsps = ranks_problem(4)
+    ex = O.exchange_to(dsps, pl, 2)
+    o = O.expert_ffn_segments(ex["recv_buf"], w1, w3, w2, ex["seg_expert"], ex["seg_counts"], ex["seg_start"])
+    for s_ in range(len(ex["seg_expert"])):
+        e = ex["seg_expert"][s_]
+        for p in range(ex["seg_start"][s_], ex["seg_start"][s_] + ex["seg_counts"][s_]):
+            np.testing.assert_allclose(o[p], scalar_ffn_row(ex["recv_buf"][p], w1[e], w3[e], w2[e]), rtol=1e-12, atol=1e-12)
+    with pytest.raises(ValueError):
+        O.expert_ffn_segments(ex["recv_buf"], w1, w3, w2, [0, 1], [3, 3], [0, 2])          # overlap
+    with pytest.raises(ValueError):
+        O.expert_ffn_segments(ex["recv_buf"], w1, w3, w2, [0], [len(ex["recv_buf"]) + 1], [0])
+    with pytest.raises(ValueError):
+        O.expert_ffn_segments(ex["recv_buf"], w1, w3, w2, [99], [1], [0])
+
+
+def test_exchange_routes_every_row_to_the_gpu_of_its_expert():
+    w1, w3, w2, pl, xs, idxs, dsps = ranks_problem(5)
+    G = 4
+    total = 0
+    for dest in range(G):
+        ex = O.exchange_to(dsps, pl, dest)
+        total += len(ex["recv_buf"])
+        assert ex["seg_counts"].sum() == len(ex["recv_buf"]) == sum(int(d["gpu_counts"][dest]) for d in dsps)
+        assert np.all(pl[ex["seg_expert"]] == dest)
+        # brute force: walk the sources' routes in their sorted order and keep those bound for dest
+        rows, experts = [], []
+        for src in range(G):
+            e_sorted = idxs[src].reshape(-1)[dsps[src]["perm"]]
+            for p, e in enumerate(e_sorted):
+                if pl[e] == dest:
+                    rows.append(xs[src][dsps[src]["perm"][p] // idxs[src].shape[1]]); experts.append(e)
+        np.testing.assert_array_equal(ex["recv_buf"], np.array(rows).reshape(len(rows), xs[0].shape[1]))
+        seg_of_row = np.repeat(ex["seg_expert"], ex["seg_counts"])
+        np.testing.assert_array_equal(seg_of_row, np.array(experts, dtype=np.int32))
+        assert np.array_equal(ex["seg_start"], np.concatenate([[0], np.cumsum(ex["seg_counts"])[:-1]]))
+    assert total == sum(x.shape[0] for x in xs) * idxs[0].shape[1]
+
+
+def test_expert_parallel_layer_equals_the_single_gpu_layer_per_source():
+    """All G receivers compute their segments, the outputs go back to the sources' bucket positions, and
+    each source combines with every expert's output present: that is the all-resident layer."""
+    w1, w3, w2, pl, xs, idxs, dsps = ranks_problem(6)
+    G, k = 4, idxs[0].shape[1]
+    back = [np.zeros((x.shape[0] * k, x.shape[1])) for x in xs]
+    for dest in range(G):
+        ex = O.exchange_to(dsps, pl, dest)
+        o = O.expert_ffn_segments(ex["recv_buf"], w1, w3, w2, ex["seg_expert"], ex["seg_counts"], ex["seg_start"])
+        for src in range(G):
+            lo = int(dsps[src]["gpu_offsets"][dest]); n = int(dsps[src]["gpu_counts"][dest])
+            back[src][lo:lo + n] = o[ex["src_offset"][src]:ex["src_offset"][src + 1]]
+    rng = np.random.default_rng(0)
+    for src in range(G):
+        w = rng.random((xs[src].shape[0], k))
+        y = O.combine(back[src], dsps[src]["inv_perm"], idxs[src], w, pl, -1)
+        single = O.expert_ffn_grouped(dsps[src]["send_buf"], w1, w3, w2, dsps[src]["expert_counts"], dsps[src]["expert_start"], pl, -1)
+        np.testing.assert_allclose(back[src], single, rtol=1e-13, atol=1e-13)
+        np.testing.assert_allclose(y, O.combine(single, dsps[src]["inv_perm"], idxs[src], w, pl, -1), rtol=1e-13, atol=1e-13)
