@@ -227,6 +227,30 @@ int moe_expert_ffn_grouped(const void* send_buf, moe_dtype_t dt,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * moe_expert_ffn_segments - the same expert FFN on the receiving side of the
+ * first all-to-all (Section 2.2 / Fig. 2b): the receive buffer is the
+ * concatenation, source GPU after source GPU, of buckets that each source
+ * sorted by expert, so an expert's rows arrive as one segment per source.
+ * Segment s is the seg_counts[s] rows of recv_buf that start at seg_start[s]
+ * and is multiplied with the weights of expert seg_expert[s]:
+ *
+ *       H = silu(A W1_e) * (A W3_e),   ffn_out[same rows] = H W2_e
+ *
+ * Several segments may name the same expert; segments must not overlap (not
+ * checked).  A segment that does not lie inside [0,N) or names an expert
+ * outside [0,E) is skipped.  seg_* are device arrays of n_seg <=
+ * MOE_MAX_EXPERTS entries, read on the device.  Everything else (dtypes,
+ * shapes, packed weights, workspace size, rows outside every segment left
+ * untouched) as in moe_expert_ffn_grouped.
+ * ---------------------------------------------------------------------- */
+int moe_expert_ffn_segments(const void* recv_buf, moe_dtype_t dt,
+                            int N, int d, int f, int E,
+                            const void* packed_weights, int n_seg,
+                            const int32_t* seg_expert, const int32_t* seg_counts,
+                            const int32_t* seg_start, void* ffn_out,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * moe_combine - un-permute and gate-weight the expert outputs (the step after
  * the second all-to-all of Fig. 2b):
  *

@@ -26,7 +26,7 @@ KERNEL_NAMES = ["gate", "dispatch_count", "dispatch_scan", "dispatch_rank", "dis
 MOE_K_COUNT = len(KERNEL_NAMES)
 
 EXPORTS = ["moe_last_error", "moe_version", "moe_topk_gate", "moe_topk_gate_norm", "moe_router_packed_bytes", "moe_pack_router", "moe_router_gate", "moe_dispatch_workspace_bytes", "moe_dispatch",
-           "moe_packed_weights_bytes", "moe_pack_weights", "moe_ffn_workspace_bytes", "moe_expert_ffn_grouped",
+           "moe_packed_weights_bytes", "moe_pack_weights", "moe_ffn_workspace_bytes", "moe_expert_ffn_grouped", "moe_expert_ffn_segments",
            "moe_combine", "moe_transition_counts", "moe_transition_counts_pairs", "moe_accumulate_counts", "moe_placement_loads",
            "moe_placement_traffic", "moe_timing_begin", "moe_timing_end"]
 
@@ -60,6 +60,7 @@ _lib.moe_pack_weights.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]
 _lib.moe_ffn_workspace_bytes.argtypes = [_i, _i, _i, _i, _i]
 _lib.moe_ffn_workspace_bytes.restype = _sz
 _lib.moe_expert_ffn_grouped.argtypes = [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]
+_lib.moe_expert_ffn_segments.argtypes = [_vp, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.moe_combine.argtypes = [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
 _lib.moe_transition_counts.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
 _lib.moe_transition_counts_pairs.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp]
@@ -166,6 +167,13 @@ def moe_expert_ffn_grouped(send_buf, dt, N, d, f, E, packed_weights, expert_coun
     _check(_lib.moe_expert_ffn_grouped(_ptr(send_buf), dt, N, d, f, E, _ptr(packed_weights), _ptr(expert_counts),
                                        _ptr(expert_start), _ptr(placement), local_gpu, _ptr(ffn_out), _ptr(workspace),
                                        workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_expert_ffn_segments(recv_buf, dt, N, d, f, E, packed_weights, n_seg, seg_expert, seg_counts, seg_start, ffn_out, workspace):
+    _dev(recv_buf, packed_weights, seg_expert, seg_counts, seg_start, ffn_out, workspace)
+    _check(_lib.moe_expert_ffn_segments(_ptr(recv_buf), dt, N, d, f, E, _ptr(packed_weights), n_seg, _ptr(seg_expert),
+                                        _ptr(seg_counts), _ptr(seg_start), _ptr(ffn_out), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream()))
 
 
 def moe_combine(ffn_out, dt, inv_perm, topk_idx, topk_w, placement, local_gpu, T, d, E, k, y):

@@ -236,9 +236,33 @@ int moe_expert_ffn_grouped(const void* send_buf, moe_dtype_t dt, int N, int d, i
     void* H = (char*)workspace + kPlanBytes;
     hipStream_t s = (hipStream_t)stream;
     if (dt == MOE_BF16)
-        return launch_ffn_bf16(send_buf, N, d, f, E, packed_weights, expert_counts, expert_start, placement, local_gpu, ffn_out, plan, H, s);
+        return launch_ffn_bf16(send_buf, N, d, f, E, packed_weights, expert_counts, expert_start, placement, local_gpu, nullptr, E,
+                               ffn_out, plan, H, s);
     return launch_ffn_f32((const float*)send_buf, N, d, f, E, (const float*)packed_weights, expert_counts, expert_start,
-                          placement, local_gpu, (float*)ffn_out, plan, (float*)H, s);
+                          placement, local_gpu, nullptr, E, (float*)ffn_out, plan, (float*)H, s);
+}
+
+int moe_expert_ffn_segments(const void* recv_buf, moe_dtype_t dt, int N, int d, int f, int E,
+                            const void* packed_weights, int n_seg, const int32_t* seg_expert, const int32_t* seg_counts,
+                            const int32_t* seg_start, void* ffn_out, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_ffn_shape("moe_expert_ffn_segments", E, d, f, dt);
+    if (rc != MOE_OK) return rc;
+    REQUIRE(N >= 0, "moe_expert_ffn_segments: N=%d < 0", N);
+    REQUIRE(n_seg >= 0 && n_seg <= MOE_MAX_EXPERTS, "moe_expert_ffn_segments: n_seg=%d outside [0,%d]", n_seg, MOE_MAX_EXPERTS);
+    if (N == 0 || n_seg == 0) return MOE_OK;
+    REQUIRE(recv_buf && packed_weights && seg_expert && seg_counts && seg_start && ffn_out && workspace,
+            "moe_expert_ffn_segments: NULL pointer");
+    REQUIRE(aligned16(recv_buf) && aligned16(packed_weights) && aligned16(ffn_out) && aligned16(workspace),
+            "moe_expert_ffn_segments: pointers must be 16-byte aligned");
+    size_t need = moe_ffn_workspace_bytes(N, d, f, E, dt);
+    if (workspace_bytes < need) return fail(MOE_ERR_WORKSPACE, "moe_expert_ffn_segments: workspace %zu < %zu bytes", workspace_bytes, need);
+    int32_t* plan = (int32_t*)workspace;
+    void* H = (char*)workspace + kPlanBytes;
+    hipStream_t s = (hipStream_t)stream;
+    if (dt == MOE_BF16)
+        return launch_ffn_bf16(recv_buf, N, d, f, n_seg, packed_weights, seg_counts, seg_start, nullptr, -1, seg_expert, E, ffn_out, plan, H, s);
+    return launch_ffn_f32((const float*)recv_buf, N, d, f, n_seg, (const float*)packed_weights, seg_counts, seg_start, nullptr, -1,
+                          seg_expert, E, (float*)ffn_out, plan, (float*)H, s);
 }
 
 int moe_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm, const int32_t* topk_idx,

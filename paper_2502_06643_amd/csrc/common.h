@@ -68,11 +68,13 @@ size_t packed_bytes_bf16(int E, int d, int f);
 size_t ffn_bf16_scratch_bytes();      // fp32 partial tiles of the split tail, sized for the largest supported XCD
 int launch_pack_f32(const float* w1, const float* w3, const float* w2, int E, int d, int f, float* packed, hipStream_t s);
 int launch_pack_bf16(const void* w1, const void* w3, const void* w2, int E, int d, int f, void* packed, hipStream_t s);
+// E row groups (counts/starts); group g uses the weights of expert group_expert[g] of n_weights
+// (g itself when group_expert is NULL)
 int launch_ffn_f32(const float* a, int N, int d, int f, int E, const float* packed, const int32_t* counts,
-                   const int32_t* starts, const int32_t* placement, int local_gpu, float* out,
-                   int32_t* plan, float* H, hipStream_t s);
+                   const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
+                   int n_weights, float* out, int32_t* plan, float* H, hipStream_t s);
 int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
-                    const int32_t* starts, const int32_t* placement, int local_gpu, void* out,
-                    int32_t* plan, void* H, hipStream_t s);
+                    const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
+                    int n_weights, void* out, int32_t* plan, void* H, hipStream_t s);
 
 }  // namespace moe

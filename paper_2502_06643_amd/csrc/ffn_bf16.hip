@@ -545,8 +545,8 @@ static int set_smem(Kernel k, int bytes) {
 // FMU / FMD: fragment rows per wavefront of the up / down projection (row tile = 128 * FM)
 template <int FMU, int FMD>
 static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
-                   const int32_t* starts, const int32_t* placement, int local_gpu, void* out,
-                   int32_t* plan, void* H, bool split_down, hipStream_t s) {
+                   const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
+                   int n_weights, void* out, int32_t* plan, void* H, bool split_down, hipStream_t s) {
     static bool configured = false;
     int rc;
     if (!configured) {
@@ -557,7 +557,7 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
         configured = true;
     }
     constexpr int BMU = Tile<FMU>::BM, BMD = Tile<FMD>::BM;
-    rc = launch_ffn_plan(counts, starts, placement, local_gpu, E, N, BMU, BMD, plan, s);
+    rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, BMU, BMD, plan, s);
     if (rc != MOE_OK) return rc;
     const int cpx = cus_per_xcd();
     const int chunk_up = row_chunk_for((size_t)N * d * 2), chunk_down = row_chunk_for((size_t)N * f * 2);
@@ -599,13 +599,13 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
 }
 
 int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
-                    const int32_t* starts, const int32_t* placement, int local_gpu, void* out,
-                    int32_t* plan, void* H, hipStream_t s) {
+                    const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
+                    int n_weights, void* out, int32_t* plan, void* H, hipStream_t s) {
     // Row tiles of 384 move about a sixth fewer bytes per flop than tiles of 256, but waste more on
     // ragged buckets; bucket sizes are only known on the device, so the choice goes by the mean.
     if ((long long)N >= 768ll * E)
-        return run_ffn<3, 3>(a, N, d, f, E, packed, counts, starts, placement, local_gpu, out, plan, H, true, s);
-    return run_ffn<2, 2>(a, N, d, f, E, packed, counts, starts, placement, local_gpu, out, plan, H, true, s);
+        return run_ffn<3, 3>(a, N, d, f, E, packed, counts, starts, placement, local_gpu, group_expert, n_weights, out, plan, H, true, s);
+    return run_ffn<2, 2>(a, N, d, f, E, packed, counts, starts, placement, local_gpu, group_expert, n_weights, out, plan, H, true, s);
 }
 
 }  // namespace moe

@@ -2,7 +2,9 @@
 // so that no bucket size ever travels to the host.
 //
 // The plan lists the experts resident on local_gpu that received at least one
-// route, largest bucket first (ties: lower expert id), with sanitised bucket
+// route (or, on the receiving side of the all-to-all, the (source GPU, expert)
+// segments of the receive buffer, each naming the expert whose weights it
+// uses), largest bucket first (ties: lower expert id), with sanitised bucket
 // bounds and, for up to two row-tile heights, the exclusive prefix of their
 // row-tile counts.  A GEMM workgroup turns a global row-tile index into
 // (expert, first row, row count) by scanning that prefix.
@@ -21,8 +23,11 @@ constexpr int kPlanInts = kPlanTiles1 + MOE_MAX_EXPERTS + 4;
 static_assert(kPlanInts * sizeof(int32_t) <= kPlanBytes, "plan area too small");
 // header: [0] number of listed experts, [1] total row tiles (bm0), [2] total row tiles (bm1)
 
+// E groups of rows (counts/starts); group g multiplies with the weights of expert group_expert[g]
+// (g itself when group_expert is NULL), of which there are n_weights; placement may be NULL when
+// local_gpu < 0.
 int launch_ffn_plan(const int32_t* counts, const int32_t* starts, const int32_t* placement, int local_gpu,
-                    int E, int N, int bm0, int bm1, int32_t* plan, hipStream_t s);
+                    const int32_t* group_expert, int n_weights, int E, int N, int bm0, int bm1, int32_t* plan, hipStream_t s);
 
 struct RowTile { int expert; int row0; int rows; };
 

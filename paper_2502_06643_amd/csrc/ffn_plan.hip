@@ -3,20 +3,22 @@
 namespace moe {
 
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ counts, const int32_t* __restrict__ starts,
-                                                       const int32_t* __restrict__ placement, int local_gpu, int E, int N,
+                                                       const int32_t* __restrict__ placement, int local_gpu,
+                                                       const int32_t* __restrict__ group_expert, int n_weights, int E, int N,
                                                        int bm0, int bm1, int32_t* __restrict__ plan) {
     __shared__ int cnt[MOE_MAX_EXPERTS];
     __shared__ int rank[MOE_MAX_EXPERTS];
     __shared__ int tiles0[MOE_MAX_EXPERTS];
     __shared__ int tiles1[MOE_MAX_EXPERTS];
     const int e = threadIdx.x;
-    int c = 0, st = 0;
+    int c = 0, st = 0, wt = e;                    // wt: whose weights this group multiplies with
     if (e < E) {
         const bool local = local_gpu < 0 || placement[e] == local_gpu;
         c = counts[e];
         st = starts[e];
-        // a bucket that does not lie inside [0,N) is ignored rather than trusted
-        if (!local || c <= 0 || st < 0 || (long long)st + c > N) c = 0;
+        if (group_expert) wt = group_expert[e];
+        // a bucket that does not lie inside [0,N), or names weights that do not exist, is ignored rather than trusted
+        if (!local || c <= 0 || st < 0 || (long long)st + c > N || (unsigned)wt >= (unsigned)n_weights) c = 0;
     }
     cnt[e] = c;
     tiles0[e] = (c + bm0 - 1) / bm0;
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
             t0 += take ? tiles0[o] : 0;
             t1 += take ? tiles1[o] : 0;
         }
-        plan[kPlanExpert + r] = e;
+        plan[kPlanExpert + r] = wt;
         plan[kPlanStart + r] = st;
         plan[kPlanCount + r] = c;
         plan[kPlanTiles0 + r] = t0;
@@ -64,9 +66,9 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
 }
 
 int launch_ffn_plan(const int32_t* counts, const int32_t* starts, const int32_t* placement, int local_gpu,
-                    int E, int N, int bm0, int bm1, int32_t* plan, hipStream_t s) {
+                    const int32_t* group_expert, int n_weights, int E, int N, int bm0, int bm1, int32_t* plan, hipStream_t s) {
     LaunchTimer timer(MOE_K_FFN_PLAN, s);
-    hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, counts, starts, placement, local_gpu, E, N, bm0, bm1, plan);
+    hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, counts, starts, placement, local_gpu, group_expert, n_weights, E, N, bm0, bm1, plan);
     return check_launch("moe_expert_ffn_grouped plan launch");
 }
 

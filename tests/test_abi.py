@@ -71,6 +71,12 @@ def test_bad_scalars_are_rejected_without_touching_the_gpu():
     assert L.moe_combine(one, 7, one, one, one, one, 0, 4, 64, 8, 2, one, None) == -1                                    # dtype
     assert L.moe_transition_counts(one, one, 4, 2, 2, 8, 8, None, None) == -1
     assert L.moe_transition_counts(one, one, 4, 9, 2, 8, 8, one, None) == -1
+    assert L.moe_expert_ffn_segments(one, 1, 8, 128, 256, 8, one, -1, one, one, one, one, one, 1 << 30, None) == -1         # n_seg < 0
+    assert L.moe_expert_ffn_segments(one, 1, 8, 128, 256, 8, one, 257, one, one, one, one, one, 1 << 30, None) == -1        # too many segments
+    assert L.moe_expert_ffn_segments(one, 1, 8, 128, 256, 8, one, 4, one, one, one, one, one, 16, None) == -3               # workspace
+    assert L.moe_expert_ffn_segments(None, 1, 8, 128, 256, 8, None, 0, None, None, None, None, None, 0, None) == 0          # no segment: nothing to do
+    assert L.moe_topk_gate_norm(one, 4, 8, 2, 5, one, one, None) == -1                                                      # unknown norm
+    assert L.moe_transition_counts_pairs(one, one, 4, 2, 2, 8, 8, 3, one, None) == -1                                       # unknown pair mode
     assert L.moe_timing_begin(1, 0) == -1
     # empty batches are fine and enqueue nothing
     assert L.moe_topk_gate(None, 0, 8, 2, None, None, None) == 0
