@@ -9,9 +9,10 @@
 // expert, or 384 x 256 when buckets are large on average; the (expert, row
 // tile) list comes from the device-side plan, so no bucket size ever reaches
 // the host.  Workgroup ids are dealt round-robin to the 8 XCDs by the hardware;
-// tile ids are assigned so that every XCD works on a contiguous range ordered
-// expert -> chunk of 4 row tiles -> column tile -> row tile: workgroups that
-// share an L2 share weight panels and activation rows.  Within a tile the rows are dealt to the four
+// every XCD owns an eighth of the column tiles of every expert (a weight panel
+// passes through one L2 only, and all XCDs see the same mix of experts) and
+// walks them expert -> chunk of row tiles -> column tile -> row tile:
+// workgroups that share an L2 share weight panels and activation rows.  Within a tile the rows are dealt to the four
 // wavefront rows in blocks of 32, and a wavefront skips the blocks that lie
 // past the end of a ragged bucket: such a tile costs ceil(rows / 128) blocks
 // per wavefront, every SIMD staying equally loaded.
@@ -159,18 +160,28 @@ struct WorkItem {
 };
 
 struct XcdShare {
-    long long t_begin;   // first tile of this XCD
+    int q, rem;          // column tiles owned outright by every XCD; left-over column tiles (NT % 8)
+    long long main;      // tiles of the owned columns: row tiles x q
+    long long rem_begin; // this XCD's first tile in the list of left-over-column tiles
     int full;            // tiles run whole
     int tail;            // tiles run in `split` k parts each
     int split;
 };
 
-__device__ __forceinline__ XcdShare xcd_share(long long total_tiles, int x, int KT, int cus_per_xcd, bool allow_split) {
+// The tiles of XCD x.  Every XCD owns NT / 8 column tiles of every expert outright, so each weight
+// panel is fetched through one L2 only and all XCDs get the same mix of large and small experts; the
+// tiles of the NT % 8 left-over column tiles are dealt to the XCDs in equal contiguous ranges.
+__device__ __forceinline__ XcdShare xcd_share(int MT, int NT, int x, int KT, int cus_per_xcd, bool allow_split) {
     XcdShare s;
-    const long long chunk = (total_tiles + kXcds - 1) / kXcds;
-    s.t_begin = (long long)x * chunk;
-    long long cnt = total_tiles - s.t_begin;
-    cnt = cnt < 0 ? 0 : (cnt > chunk ? chunk : cnt);
+    s.q = NT / kXcds;
+    s.rem = NT - s.q * kXcds;
+    s.main = (long long)MT * s.q;
+    const long long rem_total = (long long)MT * s.rem;
+    const long long chunk = (rem_total + kXcds - 1) / kXcds;
+    s.rem_begin = (long long)x * chunk;
+    long long rcnt = rem_total - s.rem_begin;
+    rcnt = rcnt < 0 ? 0 : (rcnt > chunk ? chunk : rcnt);
+    const long long cnt = s.main + rcnt;
     s.full = (int)cnt;
     s.tail = 0;
     s.split = 1;
@@ -222,6 +233,18 @@ __device__ __forceinline__ void locate_tile(const int32_t* __restrict__ plan, co
     w.expert = plan[kPlanExpert + i];
     w.row0 = plan[kPlanStart + i] + mt * BM;
     w.rows = min(BM, plan[kPlanCount + i] - mt * BM);
+}
+
+// tile `idx` of XCD x's list: first the tiles of its own column tiles, then its share of the left-over ones
+__device__ __forceinline__ void locate_xcd_tile(const int32_t* __restrict__ plan, const int32_t* __restrict__ prefix,
+                                                const XcdShare& sh, int x, int idx, int BM, int row_chunk, WorkItem& w) {
+    if (idx < sh.main) {
+        locate_tile(plan, prefix, sh.q, idx, BM, row_chunk, w);
+        w.nt += x * sh.q;
+    } else {
+        locate_tile(plan, prefix, sh.rem, sh.rem_begin + (idx - sh.main), BM, row_chunk, w);
+        w.nt += kXcds * sh.q;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -277,9 +300,13 @@ __device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* 
     constexpr int SLOTS = KB * NR * FN / kDmaEvery;
     constexpr int UPFRONT = N_DMA > SLOTS ? N_DMA - SLOTS : 0;
     const uint16_t* Bs = As + BM * BK;
-    if (UPFRONT > 0 && load) {
+    // Without `load` (the last k tile) the pieces of this same tile are fetched once more into the idle
+    // stage: the stream of matrix instructions then holds no branch at all, which is worth more than the
+    // one redundant tile per output tile costs
+    const int ktn = load ? kt + 1 : kt;
+    if (UPFRONT > 0) {
 #pragma unroll
-        for (int j = 0; j < UPFRONT; ++j) ld.issue(j, kt + 1, stage ^ 1);
+        for (int j = 0; j < UPFRONT; ++j) ld.issue(j, ktn, stage ^ 1);
     }
     // A operand: lane l holds row l % 16 and the 8 consecutive k that start at 8 * (l / 16)
     auto read_a = [&](int a, int ks) {
@@ -311,7 +338,7 @@ __device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* 
                 const int m = c * NR + a;
                 __builtin_amdgcn_sched_barrier(0);
                 if (m % kDmaEvery == kDmaEvery - 1 && UPFRONT + m / kDmaEvery < N_DMA) {
-                    if (load) ld.issue(UPFRONT + m / kDmaEvery, kt + 1, stage ^ 1);
+                    ld.issue(UPFRONT + m / kDmaEvery, ktn, stage ^ 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -438,18 +465,17 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int32_t* prefix = plan + (UP ? kPlanTiles0 : kPlanTiles1);
     const int NT = npad / BN, KT = K / BK;
-    const long long total = (long long)prefix[plan[0]] * NT;
     const int x = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
-    const XcdShare sh = xcd_share(total, x, KT, cus_per_xcd, SPLIT);
+    const XcdShare sh = xcd_share(prefix[plan[0]], NT, x, KT, cus_per_xcd, SPLIT);
     if (slot >= sh.full + sh.tail * sh.split) return;
     WorkItem w;
     if (slot < sh.full) {
-        locate_tile(plan, prefix, NT, sh.t_begin + slot, BM, row_chunk, w);
+        locate_xcd_tile(plan, prefix, sh, x, slot, BM, row_chunk, w);
         w.kt0 = 0; w.kt1 = KT; w.partial = -1;
     } else {
         const int j = slot - sh.full;
         const int part = j % sh.split;
-        locate_tile(plan, prefix, NT, sh.t_begin + sh.full + j / sh.split, BM, row_chunk, w);
+        locate_xcd_tile(plan, prefix, sh, x, sh.full + j / sh.split, BM, row_chunk, w);
         w.kt0 = (int)((long long)part * KT / sh.split);
         w.kt1 = (int)((long long)(part + 1) * KT / sh.split);
         w.partial = x * 2 * cus_per_xcd + j;
@@ -469,6 +495,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
             for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
 
     mainloop<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the pieces fetched during the last k tile land in LDS: nothing may follow them there
 
     if (SPLIT && w.partial >= 0) {
         if (nfrag > 0) {
@@ -495,12 +522,11 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     const int32_t* prefix = plan + kPlanTiles1;
     const int NT = npad / BN, KT = K / BK;
-    const long long total = (long long)prefix[plan[0]] * NT;
     const int x = blockIdx.x % kXcds, q = (blockIdx.x / kXcds) / FM, j = (blockIdx.x / kXcds) % FM;
-    const XcdShare sh = xcd_share(total, x, KT, cus_per_xcd, true);
+    const XcdShare sh = xcd_share(prefix[plan[0]], NT, x, KT, cus_per_xcd, true);
     if (q >= sh.tail) return;
     WorkItem w;
-    locate_tile(plan, prefix, NT, sh.t_begin + sh.full + q, BM, row_chunk, w);
+    locate_xcd_tile(plan, prefix, sh, x, sh.full + q, BM, row_chunk, w);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if (j >= active_blocks(w.rows, wave / WN, FM)) return;
@@ -567,8 +593,9 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
     float* partials = (float*)((char*)H + round_up((size_t)N * f * 2, 256));
     auto grid_for = [&](size_t npad, int bm, bool split) {
         const long long mt_max = (N + bm - 1) / bm + (E < N ? E : N);     // sum of ceil(n_e / bm) never exceeds this
-        const long long tiles = mt_max * (long long)(npad / BN);
-        return (long long)kXcds * ((tiles + kXcds - 1) / kXcds + (split ? 2 * cpx : 0));
+        const long long nt = (long long)(npad / BN);
+        const long long per_xcd = mt_max * (nt / kXcds) + (mt_max * (nt % kXcds) + kXcds - 1) / kXcds;
+        return (long long)kXcds * (per_xcd + (split ? 2 * cpx : 0));
     };
     {
         const long long grid = grid_for(npad13(f), BMU, false);
