@@ -73,6 +73,15 @@ int launch_pack_bf16(const void* w1, const void* w3, const void* w2, int E, int 
 int launch_ffn_f32(const float* a, int N, int d, int f, int E, const float* packed, const int32_t* counts,
                    const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
                    int n_weights, float* out, int32_t* plan, float* H, hipStream_t s);
+// bf16, N <= kFfnSkinnyMaxRows: weight-streaming kernels for decode-sized batches (plan already built).
+// Measured at the Mixtral shape with skewed top-2 routing: they win up to N = 128 rows (+13 to +18 %) and lose from
+// N = 256 on (-7 %), where the largest bucket needs several passes of 64 rows over its weights.
+#ifndef MOE_SKINNY_MAX_ROWS
+#define MOE_SKINNY_MAX_ROWS 160
+#endif
+constexpr int kFfnSkinnyMaxRows = MOE_SKINNY_MAX_ROWS;
+int launch_ffn_skinny(const void* a, int N, int d, int f, int E, const void* packed, size_t s13, size_t expert_stride,
+                      const int32_t* plan, void* H, float* partial, size_t scratch_bytes, void* out, hipStream_t s);
 int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
                     const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
                     int n_weights, void* out, int32_t* plan, void* H, hipStream_t s);

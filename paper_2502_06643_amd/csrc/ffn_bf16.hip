@@ -628,6 +628,14 @@ static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed
 int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
                     const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
                     int n_weights, void* out, int32_t* plan, void* H, hipStream_t s) {
+    if (N <= kFfnSkinnyMaxRows) {
+        // decode-sized batch: every weight is read once and hardly used; stream them without LDS or barriers
+        int rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, 256, 256, plan, s);
+        if (rc != MOE_OK) return rc;
+        const size_t s13 = npad13(f) * d, s2 = npad2(d) * f;
+        float* partials = (float*)((char*)H + round_up((size_t)N * f * 2, 256));
+        return launch_ffn_skinny(a, N, d, f, E, packed, s13, s13 + s2, plan, H, partials, ffn_bf16_scratch_bytes(), out, s);
+    }
     // Row tiles of 384 move about a sixth fewer bytes per flop than tiles of 256, but waste more on
     // ragged buckets; bucket sizes are only known on the device, so the choice goes by the mean.
     if ((long long)N >= 768ll * E)

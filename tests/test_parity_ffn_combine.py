@@ -53,6 +53,9 @@ def gpu_ffn(lib, x, w1, w3, w2, idx, pl, G, local_gpu, dtype):
     ("bf16", 1700, 128, 192, 2, 1, 1, -1),      # large mean bucket: the 384-row tile path
     ("bf16", 3000, 256, 2048, 1, 1, 1, -1),     # 384-row tiles with a k-split tail in the down projection
     ("bf16", 3000, 256, 2048, 8, 1, 2, 1),      # 256-row tiles with a k-split tail
+    ("bf16", 150, 128, 192, 1, 1, 1, -1),       # decode-sized batch, one bucket of 150 rows: three passes of the streaming kernels
+    ("bf16", 70, 64, 1408, 2, 2, 2, 1),         # decode-sized batch, one of two experts resident, k parts in the down projection
+    ("bf16", 17, 4096, 512, 8, 2, 1, -1),       # decode-sized batch at the Mixtral hidden size
 ])
 def test_ffn_matches_oracle(lib, dtype, T, d, f, E, k, G, local):
     x, w1, w3, w2, idx, pl = make_problem(T + d, T, d, f, E, k, G, dtype)
