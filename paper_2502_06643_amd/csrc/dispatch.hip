@@ -170,6 +170,100 @@ __global__ __launch_bounds__(kDispatchBlock) void dispatch_rank_kernel(const int
     }
 }
 
+// Batches of up to kFusedMaxRoutes routes: count, scan and rank in ONE workgroup of 16 wavefronts, each
+// owning a contiguous slice of the routes.  Three launches become one, which is what matters at these
+// sizes (every launch costs more than the work it does).  A thread keeps its ITEMS expert ids in
+// registers: they are loaded once, all loads in flight together, and serve both passes.  Same
+// results: positions are a pure function of the route id.
+constexpr int kFusedThreads = 1024, kFusedWaves = kFusedThreads / 64, kFusedMaxItems = 16;
+constexpr int kFusedMaxRoutes = kFusedThreads * kFusedMaxItems;
+
+template <int ITEMS>
+__global__ __launch_bounds__(kFusedThreads) void dispatch_index_kernel(const int32_t* __restrict__ topk_idx, int N, int E, int ebits,
+                                                                       const int32_t* __restrict__ placement, int G,
+                                                                       int32_t* __restrict__ expert_counts,
+                                                                       int32_t* __restrict__ expert_start,
+                                                                       int32_t* __restrict__ gpu_counts,
+                                                                       int32_t* __restrict__ gpu_offsets,
+                                                                       int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
+    // per wavefront: first the number of routes of each expert in its slice, then its running write offset
+    __shared__ int woff[kFusedWaves][MOE_MAX_EXPERTS];
+    __shared__ int pl[MOE_MAX_EXPERTS];
+    __shared__ int tot[MOE_MAX_EXPERTS];
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    for (int i = threadIdx.x; i < kFusedWaves * MOE_MAX_EXPERTS; i += kFusedThreads) (&woff[0][0])[i] = 0;
+    if (threadIdx.x < E) pl[threadIdx.x] = placement[threadIdx.x];
+    __syncthreads();
+
+    const int wbase = wave * ITEMS * 64;                                // ITEMS 64-route steps per wavefront
+    const unsigned long long lower = (1ull << lane) - 1ull;
+    volatile int* my = woff[wave];
+    int exs[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int r = wbase + i * 64 + lane;
+        exs[i] = (r < N) ? topk_idx[r] : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i)
+        if ((unsigned)exs[i] < (unsigned)E) atomicAdd(&woff[wave][exs[i]], 1);   // LDS atomics: counts need no order
+    __syncthreads();
+    if (threadIdx.x < E) {
+        int t = 0;
+#pragma unroll
+        for (int w = 0; w < kFusedWaves; ++w) t += woff[w][threadIdx.x];
+        tot[threadIdx.x] = t;
+        expert_counts[threadIdx.x] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x < E) {
+        const int me = threadIdx.x, ge = pl[me];
+        int start = 0;
+#pragma unroll 8
+        for (int o = 0; o < E; ++o) {
+            const int go = pl[o];
+            start += ((go < ge) | ((go == ge) & (o < me))) ? tot[o] : 0;
+        }
+        expert_start[me] = start;
+        int run = start;
+#pragma unroll
+        for (int w = 0; w < kFusedWaves; ++w) {
+            const int c = woff[w][me];
+            woff[w][me] = run;
+            run += c;
+        }
+    }
+    for (int g = threadIdx.x; g < G; g += kFusedThreads) {
+        int cnt = 0, off = 0;
+#pragma unroll 8
+        for (int o = 0; o < E; ++o) {
+            const int go = pl[o], to = tot[o];
+            cnt += (go == g) ? to : 0;
+            off += ((go >= 0) & (go < g)) ? to : 0;
+        }
+        gpu_counts[g] = cnt;
+        gpu_offsets[g] = off;
+        if (g == G - 1) gpu_offsets[G] = off + cnt;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int r = wbase + i * 64 + lane;
+        const int ex = exs[i];
+        const bool ok = (unsigned)ex < (unsigned)E;
+        const unsigned long long m = match_expert(ex, ok, ebits);
+        int pos = 0;
+        if (ok) pos = my[ex] + __popcll(m & lower);
+        __builtin_amdgcn_wave_barrier();
+        if (ok && (m & lower) == 0ull) my[ex] += __popcll(m);
+        __builtin_amdgcn_wave_barrier();
+        if (ok) {
+            perm[pos] = (int32_t)r;
+            inv_perm[r] = pos;
+        }
+    }
+}
+
 // One thread per 16-byte unit of a source row: read once, write k times.
 __global__ __launch_bounds__(256) void dispatch_rows_kernel(const uint4* __restrict__ x, long long total_units, int units_per_row,
                                                             int k, int N, const int32_t* __restrict__ inv_perm,
@@ -196,22 +290,36 @@ int launch_dispatch(const void* x, int row_bytes, const int32_t* topk_idx, int T
     while ((1 << ebits) < E) ++ebits;
     const int EP = 1 << ebits;
     int rc;
-    if (nblocks > 0) {
-        LaunchTimer timer(MOE_K_DISPATCH_COUNT, s);
-        hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, items, block_counts);
-        if ((rc = check_launch("moe_dispatch count launch")) != MOE_OK) return rc;
-    }
-    {
-        LaunchTimer timer(MOE_K_DISPATCH_SCAN, s);
-        hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, block_counts, nblocks, E, EP, placement, G,
-                           expert_counts, expert_start, gpu_counts, gpu_offsets);
-        if ((rc = check_launch("moe_dispatch scan launch")) != MOE_OK) return rc;
-    }
-    if (nblocks > 0) {
+    if (N <= kFusedMaxRoutes) {
         LaunchTimer timer(MOE_K_DISPATCH_RANK, s);
-        hipLaunchKernelGGL(dispatch_rank_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, ebits, items,
-                           block_counts, expert_start, perm, inv_perm);
-        if ((rc = check_launch("moe_dispatch rank launch")) != MOE_OK) return rc;
+#define MOE_LAUNCH_INDEX(ITEMS)                                                                                          \
+    hipLaunchKernelGGL(dispatch_index_kernel<ITEMS>, dim3(1), dim3(kFusedThreads), 0, s, topk_idx, N, E, ebits, placement, G, \
+                       expert_counts, expert_start, gpu_counts, gpu_offsets, perm, inv_perm)
+        if (N <= kFusedThreads) MOE_LAUNCH_INDEX(1);
+        else if (N <= 2 * kFusedThreads) MOE_LAUNCH_INDEX(2);
+        else if (N <= 4 * kFusedThreads) MOE_LAUNCH_INDEX(4);
+        else if (N <= 8 * kFusedThreads) MOE_LAUNCH_INDEX(8);
+        else MOE_LAUNCH_INDEX(kFusedMaxItems);
+#undef MOE_LAUNCH_INDEX
+        if ((rc = check_launch("moe_dispatch index launch")) != MOE_OK) return rc;
+    } else {
+        if (nblocks > 0) {
+            LaunchTimer timer(MOE_K_DISPATCH_COUNT, s);
+            hipLaunchKernelGGL(dispatch_count_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, items, block_counts);
+            if ((rc = check_launch("moe_dispatch count launch")) != MOE_OK) return rc;
+        }
+        {
+            LaunchTimer timer(MOE_K_DISPATCH_SCAN, s);
+            hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, block_counts, nblocks, E, EP, placement, G,
+                               expert_counts, expert_start, gpu_counts, gpu_offsets);
+            if ((rc = check_launch("moe_dispatch scan launch")) != MOE_OK) return rc;
+        }
+        if (nblocks > 0) {
+            LaunchTimer timer(MOE_K_DISPATCH_RANK, s);
+            hipLaunchKernelGGL(dispatch_rank_kernel, dim3(nblocks), dim3(kDispatchBlock), 0, s, topk_idx, N, E, ebits, items,
+                               block_counts, expert_start, perm, inv_perm);
+            if ((rc = check_launch("moe_dispatch rank launch")) != MOE_OK) return rc;
+        }
     }
     if (x != nullptr && N > 0) {
         const int units_per_row = row_bytes / 16;

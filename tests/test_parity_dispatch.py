@@ -82,6 +82,16 @@ def test_empty_batch(lib):
     assert not got["expert_start"].any()
 
 
+@pytest.mark.parametrize("T,E,k,G", [(70000, 8, 3, 4), (40000, 64, 6, 8), (16384, 8, 1, 4), (16385, 8, 1, 4), (4097, 8, 1, 2)])
+def test_large_batches_take_the_multi_workgroup_path(lib, T, E, k, G):
+    """Above 16384 routes the index build runs as count / scan / rank kernels
+    over many workgroups instead of one fused workgroup (sizes on both sides
+    of the switch); index-only mode."""
+    rng = np.random.default_rng(T + E)
+    pl = rng.integers(0, G, E).astype(np.int32)
+    check(lib, None, synth.random_topk_idx(T % 1000 + E, T, E, k), pl, G)
+
+
 @pytest.mark.parametrize("name", ["c2", "c2b", "c3", "c4", "c5"])
 def test_config_shapes_full_size(lib, name):
     """Full-size batches with the skewed routing of the benchmark configs
