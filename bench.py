@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # Bytes that cross the L2 boundary per launch of the dominant kernel (up projection), from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain 1 GiB copy of known size; the summary
 # and the commands are in profiles/bench_c2_rocprofv3.md.  Only known for the default workload.
-MEASURED_TRAFFIC_BYTES = {"c2": 4044.2e6 + 234.9e6}
+MEASURED_TRAFFIC_BYTES = {"c2": 4398.4e6 + 234.9e6}
 
 
 def cpu_baseline(cfg, x, lg, weights, pl, budget_rows=8192):
@@ -149,6 +149,14 @@ def main():
     roofline = {"bound": "mfma", "kernel": "ffn_up (A.[W1|W3] + SwiGLU)", "achieved": round(achieved, 2), "peak": peak,
                 "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
                 "ms": round(up_ms, 4), "flops_per_launch": up_flops}
+    if cfg.dtype == "bf16" and cfg.T * cfg.k <= B.FFN_STREAMING_MAX_ROWS:
+        # decode-sized batch: the up projection streams every touched expert's W1 and W3 once and is bound by HBM
+        touched = int((counts > 0).sum() if cfg.local_gpu < 0 else (counts[pl == cfg.local_gpu] > 0).sum())
+        up_bytes = touched * 2.0 * cfg.d * cfg.f * elt + n_local * (cfg.d + cfg.f) * elt
+        gbs = up_bytes / (up_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "ffn_up (weight streaming, decode-sized batch)", "achieved": round(gbs, 1),
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
+                    "ms": round(up_ms, 4), "bytes_per_launch": up_bytes}
 
     out = {
         "metric": "MoE-layer tokens/s on 1 MI355X (Mixtral-8x7B shape)", "value": round(cfg.T / (ms_per_step * 1e-3), 1),

@@ -21,6 +21,7 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_NORM_SOFTMAX_SELECTED, MOE_NORM_SOFTMAX_ALL = 0, 1
 MOE_PAIRS_ALL, MOE_PAIRS_TOP1 = 0, 1
 MOE_MAX_EXPERTS, MOE_MAX_GPUS, MOE_MAX_TOPK = 256, 256, 16
+FFN_STREAMING_MAX_ROWS = 160      # bf16 batches of at most this many routes run the weight-streaming FFN kernels
 KERNEL_NAMES = ["gate", "dispatch_count", "dispatch_scan", "dispatch_rank", "dispatch_rows",
                 "ffn_plan", "ffn_up", "ffn_down", "combine", "transition", "router"]
 MOE_K_COUNT = len(KERNEL_NAMES)
