@@ -53,6 +53,24 @@ __global__ __launch_bounds__(256) void transition_kernel(const int32_t* __restri
             }
         }
     }
+    if (use_l <= 8 && use_l1 <= 8) {
+        // up to 8 x 8 pairs per token: both index lists go to registers first (all loads in flight together;
+        // slots past use_l / use_l1 hold -1, which count() ignores)
+        for (; t < T; t += stride) {
+            int e1s[8], e2s[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                e1s[j] = j < use_l ? idx_l[t * k_l + j] : -1;
+                e2s[j] = j < use_l1 ? idx_l1[t * k_l1 + j] : -1;
+            }
+#pragma unroll
+            for (int j1 = 0; j1 < 8; ++j1) {
+                if (j1 >= use_l) break;
+#pragma unroll
+                for (int j2 = 0; j2 < 8; ++j2) count(e1s[j1], e2s[j2]);
+            }
+        }
+    }
     for (; t < T; t += stride) {
         for (int j1 = 0; j1 < use_l; ++j1) {              // the first use_l of the k_l slots (all of them, or the top-1)
             const int e1 = idx_l[t * k_l + j1];
@@ -75,7 +93,10 @@ int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_
     const int use_l = top1_only ? 1 : k_l, use_l1 = top1_only ? 1 : k_l1;
     const int pairs_of_two = k_l == 2 && k_l1 == 2 && ((uintptr_t)idx_l & 7) == 0 && ((uintptr_t)idx_l1 & 7) == 0;
     const int bins = E_l * E_l1;
-    long long want = ((long long)T + 256 * kTokPerThread - 1) / (256 * kTokPerThread);
+    // tokens per thread: four for top-2 x top-2, one when a token has 16 pairs or more
+    const int pairs = use_l * use_l1;
+    const int tpt = pairs >= 16 ? 1 : (pairs >= 8 ? 2 : kTokPerThread);
+    long long want = ((long long)T + 256 * tpt - 1) / (256 * tpt);
     const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 512 ? 512 : want));
     int copies = 1;
     while (copies < 32 && bins * copies * 2 <= kLdsBins) copies *= 2;
