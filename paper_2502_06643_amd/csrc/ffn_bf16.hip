@@ -85,7 +85,7 @@ template <int FM> struct Tile {
 constexpr int kPanelCols = 16;
 constexpr int kXcds = 8;
 constexpr int kMaxSplit = 8;
-constexpr int kMinSplitKT = 16;                 // a k part is at least this many k tiles
+constexpr int kMinSplitKT = 8;                  // a k part is at least this many k tiles
 constexpr size_t kMaxPartialFloats = (size_t)384 * BN;          // one fp32 partial tile of the largest tile
 
 static inline size_t npad13(int f) { return round_up((size_t)2 * f, BN); }
@@ -463,7 +463,8 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
                                                             int cus_per_xcd, int row_chunk) {
     constexpr int BM = Tile<FM>::BM;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    const int32_t* prefix = plan + (UP ? kPlanTiles0 : kPlanTiles1);
+    if (plan[3] != (FM == 3 ? 0 : 1)) return;            // the plan chose the other tile height
+    const int32_t* prefix = plan + (FM == 3 ? kPlanTiles0 : kPlanTiles1);
     const int NT = npad / BN, KT = K / BK;
     const int x = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
     const XcdShare sh = xcd_share(prefix[plan[0]], NT, x, KT, cus_per_xcd, SPLIT);
@@ -520,7 +521,8 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
                                                                   const float* __restrict__ partials, int cus_per_xcd, int row_chunk) {
     constexpr int BM = Tile<FM>::BM;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    const int32_t* prefix = plan + kPlanTiles1;
+    if (plan[3] != (FM == 3 ? 0 : 1)) return;
+    const int32_t* prefix = plan + (FM == 3 ? kPlanTiles0 : kPlanTiles1);
     const int NT = npad / BN, KT = K / BK;
     const int x = blockIdx.x % kXcds, q = (blockIdx.x / kXcds) / FM, j = (blockIdx.x / kXcds) % FM;
     const XcdShare sh = xcd_share(prefix[plan[0]], NT, x, KT, cus_per_xcd, true);
@@ -568,79 +570,102 @@ static int set_smem(Kernel k, int bytes) {
     return e == hipSuccess ? MOE_OK : hip_fail(e, "hipFuncSetAttribute");
 }
 
-// FMU / FMD: fragment rows per wavefront of the up / down projection (row tile = 128 * FM)
-template <int FMU, int FMD>
-static int run_ffn(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
-                   const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
-                   int n_weights, void* out, int32_t* plan, void* H, bool split_down, hipStream_t s) {
-    static bool configured = false;
-    int rc;
-    if (!configured) {
-        if ((rc = set_smem(&ffn_bf16_kernel<true, false, FMU>, smem_bytes<true, FMU>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_kernel<false, false, FMD>, smem_bytes<false, FMD>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_kernel<false, true, FMD>, smem_bytes<false, FMD>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_fixup_kernel<FMD>, epilogue_bytes<false>())) != MOE_OK) return rc;
-        configured = true;
-    }
-    constexpr int BMU = Tile<FMU>::BM, BMD = Tile<FMD>::BM;
-    rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, BMU, BMD, plan, s);
-    if (rc != MOE_OK) return rc;
-    const int cpx = cus_per_xcd();
-    const int chunk_up = row_chunk_for((size_t)N * d * 2), chunk_down = row_chunk_for((size_t)N * f * 2);
-    const size_t s13 = npad13(f) * d, s2 = npad2(d) * f, stride = s13 + s2;
-    const uint16_t* Wp = (const uint16_t*)packed;
-    // partial tiles live behind H in the workspace
-    float* partials = (float*)((char*)H + round_up((size_t)N * f * 2, 256));
-    auto grid_for = [&](size_t npad, int bm, bool split) {
+struct FfnCall {
+    const void* a; int N, d, f, E; const void* packed; void* out; int32_t* plan; void* H; hipStream_t s;
+    int cpx, chunk_up, chunk_down;
+    size_t s13, stride;
+    float* partials;
+    long long grid_for(size_t npad, int bm, bool split) const {
         const long long mt_max = (N + bm - 1) / bm + (E < N ? E : N);     // sum of ceil(n_e / bm) never exceeds this
         const long long nt = (long long)(npad / BN);
         const long long per_xcd = mt_max * (nt / kXcds) + (mt_max * (nt % kXcds) + kXcds - 1) / kXcds;
         return (long long)kXcds * (per_xcd + (split ? 2 * cpx : 0));
-    };
-    {
-        const long long grid = grid_for(npad13(f), BMU, false);
-        if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
-        LaunchTimer timer(MOE_K_FFN_UP, s);
-        hipLaunchKernelGGL((ffn_bf16_kernel<true, false, FMU>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<true, FMU>()), s,
-                           (const uint16_t*)a, Wp, stride, d, (int)npad13(f), (uint16_t*)H, f, plan, partials, cpx, chunk_up);
-        if ((rc = check_launch("moe_expert_ffn_grouped up launch")) != MOE_OK) return rc;
     }
-    {
-        const long long grid = grid_for(npad2(d), BMD, split_down);
-        if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
-        LaunchTimer timer(MOE_K_FFN_DOWN, s);
-        if (split_down) {
-            hipLaunchKernelGGL((ffn_bf16_kernel<false, true, FMD>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FMD>()), s,
-                               (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
-            if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
-            hipLaunchKernelGGL(ffn_bf16_fixup_kernel<FMD>, dim3(kXcds * cpx * FMD), dim3(kThreads), (epilogue_bytes<false>()), s, f,
-                               (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
-            if ((rc = check_launch("moe_expert_ffn_grouped fix-up launch")) != MOE_OK) return rc;
-        } else {
-            hipLaunchKernelGGL((ffn_bf16_kernel<false, false, FMD>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FMD>()), s,
-                               (const uint16_t*)H, Wp + s13, stride, f, (int)npad2(d), (uint16_t*)out, d, plan, partials, cpx, chunk_down);
-            if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
-        }
+};
+
+// the two projections on row tiles of 128 * FM rows (FM fragment rows per wavefront); the kernels
+// return at once when the plan chose the other tile height
+template <int FM>
+static int configure() {
+    static bool configured = false;
+    int rc;
+    if (!configured) {
+        if ((rc = set_smem(&ffn_bf16_kernel<true, false, FM>, smem_bytes<true, FM>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_kernel<false, true, FM>, smem_bytes<false, FM>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_fixup_kernel<FM>, epilogue_bytes<false>())) != MOE_OK) return rc;
+        configured = true;
     }
     return MOE_OK;
+}
+
+template <int FM>
+static int run_up(const FfnCall& c) {
+    int rc = configure<FM>();
+    if (rc != MOE_OK) return rc;
+    const long long grid = c.grid_for(npad13(c.f), Tile<FM>::BM, false);
+    if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
+    hipLaunchKernelGGL((ffn_bf16_kernel<true, false, FM>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<true, FM>()), c.s,
+                       (const uint16_t*)c.a, (const uint16_t*)c.packed, c.stride, c.d, (int)npad13(c.f), (uint16_t*)c.H, c.f, c.plan,
+                       c.partials, c.cpx, c.chunk_up);
+    return check_launch("moe_expert_ffn_grouped up launch");
+}
+
+template <int FM>
+static int run_down(const FfnCall& c) {
+    int rc = configure<FM>();
+    if (rc != MOE_OK) return rc;
+    const long long grid = c.grid_for(npad2(c.d), Tile<FM>::BM, true);
+    if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
+    const uint16_t* W2 = (const uint16_t*)c.packed + c.s13;
+    hipLaunchKernelGGL((ffn_bf16_kernel<false, true, FM>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FM>()), c.s,
+                       (const uint16_t*)c.H, W2, c.stride, c.f, (int)npad2(c.d), (uint16_t*)c.out, c.d, c.plan, c.partials, c.cpx,
+                       c.chunk_down);
+    if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
+    hipLaunchKernelGGL(ffn_bf16_fixup_kernel<FM>, dim3(kXcds * c.cpx * FM), dim3(kThreads), (epilogue_bytes<false>()), c.s, c.f,
+                       (int)npad2(c.d), (uint16_t*)c.out, c.d, c.plan, c.partials, c.cpx, c.chunk_down);
+    return check_launch("moe_expert_ffn_grouped fix-up launch");
 }
 
 int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packed, const int32_t* counts,
                     const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
                     int n_weights, void* out, int32_t* plan, void* H, hipStream_t s) {
+    int rc;
     if (N <= kFfnSkinnyMaxRows) {
         // decode-sized batch: every weight is read once and hardly used; stream them without LDS or barriers
-        int rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, 256, 256, plan, s);
+        rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, 256, 256, 0, plan, s);
         if (rc != MOE_OK) return rc;
         const size_t s13 = npad13(f) * d, s2 = npad2(d) * f;
         float* partials = (float*)((char*)H + round_up((size_t)N * f * 2, 256));
         return launch_ffn_skinny(a, N, d, f, E, packed, s13, s13 + s2, plan, H, partials, ffn_bf16_scratch_bytes(), out, s);
     }
     // Row tiles of 384 move about a sixth fewer bytes per flop than tiles of 256, but waste more on
-    // ragged buckets; bucket sizes are only known on the device, so the choice goes by the mean.
-    if ((long long)N >= 768ll * E)
-        return run_ffn<3, 3>(a, N, d, f, E, packed, counts, starts, placement, local_gpu, group_expert, n_weights, out, plan, H, true, s);
-    return run_ffn<2, 2>(a, N, d, f, E, packed, counts, starts, placement, local_gpu, group_expert, n_weights, out, plan, H, true, s);
+    // ragged buckets and leave compute units idle when there are few tiles: 384 when the resident buckets
+    // hold kLargeBucketRows rows or more on average.  When every row is in a resident bucket the host
+    // knows that average; otherwise only the device does (the plan decides), and the kernels of both tile
+    // heights are launched: those of the height not chosen return at once.
+    const bool every_row_resident = local_gpu < 0 && group_expert == nullptr;
+    const int choice = every_row_resident ? ((long long)N >= (long long)kLargeBucketRows * E ? 0 : 1) : -1;
+    rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, Tile<3>::BM, Tile<2>::BM, choice, plan, s);
+    if (rc != MOE_OK) return rc;
+    FfnCall c;
+    c.a = a; c.N = N; c.d = d; c.f = f; c.E = E; c.packed = packed; c.out = out; c.plan = plan; c.H = H; c.s = s;
+    c.cpx = cus_per_xcd();
+    c.chunk_up = row_chunk_for((size_t)N * d * 2);
+    c.chunk_down = row_chunk_for((size_t)N * f * 2);
+    c.s13 = npad13(f) * d;
+    c.stride = c.s13 + npad2(d) * f;
+    c.partials = (float*)((char*)H + round_up((size_t)N * f * 2, 256));     // partial tiles live behind H in the workspace
+    {
+        LaunchTimer timer(MOE_K_FFN_UP, s);
+        if (choice != 1 && (rc = run_up<3>(c)) != MOE_OK) return rc;
+        if (choice != 0 && (rc = run_up<2>(c)) != MOE_OK) return rc;
+    }
+    {
+        LaunchTimer timer(MOE_K_FFN_DOWN, s);
+        if (choice != 1 && (rc = run_down<3>(c)) != MOE_OK) return rc;
+        if (choice != 0 && (rc = run_down<2>(c)) != MOE_OK) return rc;
+    }
+    return MOE_OK;
 }
 
 }  // namespace moe

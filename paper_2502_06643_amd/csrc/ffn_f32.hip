@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
 int launch_ffn_f32(const float* a, int N, int d, int f, int E, const float* packed, const int32_t* counts,
                    const int32_t* starts, const int32_t* placement, int local_gpu, const int32_t* group_expert,
                    int n_weights, float* out, int32_t* plan, float* H, hipStream_t s) {
-    int rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, FBM, FBM, plan, s);
+    int rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, FBM, FBM, 0, plan, s);
     if (rc != MOE_OK) return rc;
     const int mt_max = (N + FBM - 1) / FBM + (E < N ? E : N);     // sum of ceil(n_e/BM) never exceeds this
     if (mt_max > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: fp32 path supports at most %d routes", (65535 - 256) * FBM);

@@ -21,13 +21,18 @@ constexpr int kPlanTiles0 = kPlanCount + MOE_MAX_EXPERTS;      // [257] prefix f
 constexpr int kPlanTiles1 = kPlanTiles0 + MOE_MAX_EXPERTS + 4; // [257] prefix for tile height bm1
 constexpr int kPlanInts = kPlanTiles1 + MOE_MAX_EXPERTS + 4;
 static_assert(kPlanInts * sizeof(int32_t) <= kPlanBytes, "plan area too small");
-// header: [0] number of listed experts, [1] total row tiles (bm0), [2] total row tiles (bm1)
+// header: [0] number of listed experts, [1] total row tiles (bm0), [2] total row tiles (bm1),
+//         [3] which of the two tile heights the bf16 GEMMs use: 0 = bm0, 1 = bm1 (see `choice`)
 
 // E groups of rows (counts/starts); group g multiplies with the weights of expert group_expert[g]
 // (g itself when group_expert is NULL), of which there are n_weights; placement may be NULL when
 // local_gpu < 0.
+// choice: 0 or 1 fixes header [3]; -1 lets the device decide from the listed buckets: bm0 when they hold
+// at least kLargeBucketRows rows on average, else bm1.
+constexpr int kLargeBucketRows = 768;
 int launch_ffn_plan(const int32_t* counts, const int32_t* starts, const int32_t* placement, int local_gpu,
-                    const int32_t* group_expert, int n_weights, int E, int N, int bm0, int bm1, int32_t* plan, hipStream_t s);
+                    const int32_t* group_expert, int n_weights, int E, int N, int bm0, int bm1, int choice, int32_t* plan,
+                    hipStream_t s);
 
 struct RowTile { int expert; int row0; int rows; };
 

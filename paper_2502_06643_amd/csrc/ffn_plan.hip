@@ -5,7 +5,7 @@ namespace moe {
 __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict__ counts, const int32_t* __restrict__ starts,
                                                        const int32_t* __restrict__ placement, int local_gpu,
                                                        const int32_t* __restrict__ group_expert, int n_weights, int E, int N,
-                                                       int bm0, int bm1, int32_t* __restrict__ plan) {
+                                                       int bm0, int bm1, int choice, int32_t* __restrict__ plan) {
     __shared__ __attribute__((aligned(16))) int cnt[MOE_MAX_EXPERTS];
     __shared__ __attribute__((aligned(16))) int rank[MOE_MAX_EXPERTS];
     __shared__ __attribute__((aligned(16))) int tiles0[MOE_MAX_EXPERTS];
@@ -57,27 +57,31 @@ __global__ __launch_bounds__(256) void ffn_plan_kernel(const int32_t* __restrict
     }
     if (e == 0) {
         int n = 0, t0 = 0, t1 = 0;
+        long long rows = 0;
         const int4* cnt4 = reinterpret_cast<const int4*>(cnt);
         const int4* tl0 = reinterpret_cast<const int4*>(tiles0);
         const int4* tl1 = reinterpret_cast<const int4*>(tiles1);
         for (int q = 0; q < E4; ++q) {
             const int4 co = cnt4[q], a = tl0[q], b = tl1[q];
             n += (co.x > 0) + (co.y > 0) + (co.z > 0) + (co.w > 0);
+            rows += (long long)co.x + co.y + co.z + co.w;
             t0 += a.x + a.y + a.z + a.w;
             t1 += b.x + b.y + b.z + b.w;
         }
         plan[0] = n;
         plan[1] = t0;
         plan[2] = t1;
+        plan[3] = choice >= 0 ? choice : (rows >= (long long)kLargeBucketRows * n ? 0 : 1);
         plan[kPlanTiles0 + n] = t0;
         plan[kPlanTiles1 + n] = t1;
     }
 }
 
 int launch_ffn_plan(const int32_t* counts, const int32_t* starts, const int32_t* placement, int local_gpu,
-                    const int32_t* group_expert, int n_weights, int E, int N, int bm0, int bm1, int32_t* plan, hipStream_t s) {
+                    const int32_t* group_expert, int n_weights, int E, int N, int bm0, int bm1, int choice, int32_t* plan,
+                    hipStream_t s) {
     LaunchTimer timer(MOE_K_FFN_PLAN, s);
-    hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, counts, starts, placement, local_gpu, group_expert, n_weights, E, N, bm0, bm1, plan);
+    hipLaunchKernelGGL(ffn_plan_kernel, dim3(1), dim3(256), 0, s, counts, starts, placement, local_gpu, group_expert, n_weights, E, N, bm0, bm1, choice, plan);
     return check_launch("moe_expert_ffn_grouped plan launch");
 }
 
