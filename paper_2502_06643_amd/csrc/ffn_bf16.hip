@@ -396,6 +396,80 @@ __device__ __forceinline__ void mainloop(f32x4 (&acc)[2 * FM][FN], uint16_t* sme
     else kloop<FM, 0>(acc, smem, ld, w, wave_m, wave_n, lane);
 }
 
+// Tiles of at most kSmallRows rows (the ragged last tile of a bucket, small buckets): there is next to no
+// matrix work to hide the loads behind, so with two stages every k tile costs a full memory round trip
+// (measured: an 18-row tile takes 93 us where a full one takes 137).  Such a tile needs only a third of the
+// activation space, so its stages are 48 KB and three of them fit: two k tiles are in flight while one is
+// multiplied.  Row block 0 of every wavefront row covers the tile (rows 32 * wave_m .. +31).  Used by the
+// up projection only: in the down projection it gained at some batch sizes and lost at others (the small
+// tiles then take bandwidth from the large bucket's tiles, which finish last).
+constexpr int kSmallRows = 128, kSmallStages = 3;
+constexpr int kSmallAChunks = kSmallRows / 8, kSmallAPerWave = kSmallAChunks / NW;
+constexpr int kSmallStage = (kSmallRows + BN) * BK;                     // elements per stage
+constexpr int kSmallDma = kSmallAPerWave + B_PER_WAVE;                   // pieces per wavefront and k tile
+static_assert(kSmallDma == 6, "the wait below counts six pieces per k tile");
+
+template <int FM>
+__device__ __forceinline__ void mainloop_small(f32x4 (&acc)[2 * FM][FN], uint16_t* smem, const uint16_t* __restrict__ A,
+                                               const uint16_t* __restrict__ Bbase, int K, const WorkItem& w, int wave, int lane,
+                                               bool has_rows) {
+    const int wave_m = wave / WN, wave_n = wave % WN;
+    uint32_t a_voff[kSmallAPerWave], b_voff[B_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < kSmallAPerWave; ++j) {
+        const int r = (wave + j * NW) * 8 + (lane >> 3);
+        a_voff[j] = (uint32_t)min(r, w.rows - 1) * (uint32_t)K * 2u + (uint32_t)swz(r, lane & 7) * 16u;
+    }
+#pragma unroll
+    for (int j = 0; j < B_PER_WAVE; ++j) b_voff[j] = (uint32_t)(wave + j * NW) * 1024u + (uint32_t)lane * 16u;
+    const uint16_t* Abase = A + (size_t)w.row0 * K;
+    const uint32_t lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem + (uint32_t)wave * 1024u;
+    auto issue_tile = [&](int kt, int st) {
+        const uint32_t l = lds + (uint32_t)st * (kSmallStage * 2);
+#pragma unroll
+        for (int j = 0; j < kSmallAPerWave; ++j) dma16(a_voff[j], Abase + (size_t)kt * BK, l + j * NW * 1024);
+#pragma unroll
+        for (int j = 0; j < B_PER_WAVE; ++j) dma16(b_voff[j], Bbase + (size_t)kt * (BK * BN), l + (kSmallAChunks + j * NW) * 1024);
+    };
+    const int n = w.kt1 - w.kt0;
+    issue_tile(w.kt0, 0);
+    if (n > 1) issue_tile(w.kt0 + 1, 1);
+    int st = 0;
+    for (int i = 0; i < n; ++i) {
+        // tile i has landed (the pieces of tile i+1 may still be in flight: six per wavefront, in order)
+        if (i + 1 < n) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                                     // everyone's pieces have, and tile i-1 has been consumed
+        if (i + 2 < n) issue_tile(w.kt0 + i + 2, st == 0 ? 2 : st - 1);      // into the stage of tile i-1
+        if (has_rows) {
+            const uint16_t* As = smem + st * kSmallStage;
+            const uint16_t* Bs = As + kSmallRows * BK;
+            // all fragments of the k tile are read before the first matrix instruction (registers are plentiful
+            // on this path): one LDS round trip per k tile instead of one per column
+            bf16x8 af[KB][2], bq[KB][FN];
+#pragma unroll
+            for (int ks = 0; ks < KB; ++ks) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    const int r = wave_m * 32 + a * 16 + (lane & 15);
+                    af[ks][a] = *reinterpret_cast<const bf16x8*>(As + r * BK + swz(r, ks * 4 + (lane >> 4)) * 8);
+                }
+#pragma unroll
+                for (int b = 0; b < FN; ++b)
+                    bq[ks][b] = *reinterpret_cast<const bf16x8*>(Bs + ((wave_n * FN + b) * KB + ks) * 512 + lane * 8);
+            }
+#pragma unroll
+            for (int ks = 0; ks < KB; ++ks)
+#pragma unroll
+                for (int b = 0; b < FN; ++b) {
+                    acc[0][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][0], bq[ks][b], acc[0][b], 0, 0, 0);
+                    acc[1][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][1], bq[ks][b], acc[1][b], 0, 0, 0);
+                }
+        }
+        st = st == 2 ? 0 : st + 1;
+    }
+}
+
 // accumulators -> bf16 -> per-wavefront LDS staging tile (32 rows at a time) -> 16-byte stores of
 // whole lines.  accumulator v of a 16x16 fragment: row 4 * (lane / 16) + v, column lane % 16.
 // One 32-row block (two fragment rows, blk[0] and blk[1]) whose first tile row is row_base:
@@ -452,8 +526,9 @@ constexpr int epilogue_bytes() { return NW * 32 * ((UP ? WTN / 2 : WTN) + 8) * 2
 
 template <bool UP, int FM>
 constexpr int smem_bytes() {
-    constexpr int stage_bytes = NS * Tile<FM>::STAGE * 2;
-    return stage_bytes > epilogue_bytes<UP>() ? stage_bytes : epilogue_bytes<UP>();
+    constexpr int stage_bytes = NS * Tile<FM>::STAGE * 2, small_bytes = kSmallStages * kSmallStage * 2;
+    constexpr int loop_bytes = stage_bytes > small_bytes ? stage_bytes : small_bytes;
+    return loop_bytes > epilogue_bytes<UP>() ? loop_bytes : epilogue_bytes<UP>();
 }
 
 template <bool UP, bool SPLIT, int FM>
@@ -495,7 +570,8 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
 
-    mainloop<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag);
+    if (UP && w.rows <= kSmallRows) mainloop_small<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag > 0);
+    else mainloop<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the pieces fetched during the last k tile land in LDS: nothing may follow them there
 
     if (SPLIT && w.partial >= 0) {
