@@ -76,15 +76,7 @@ __global__ __launch_bounds__(256) void combine_token_kernel(const uint4* __restr
     for (int i = 0; i < UNITS_PER_THREAD; ++i)
 #pragma unroll
         for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
-    for (int j = 0; j < k; ++j) {
-        const long long r = t * k + j;
-        if (local_gpu >= 0) {
-            const int e = topk_idx[r];
-            if ((unsigned)e >= (unsigned)E || placement[e] != local_gpu) continue;
-        }
-        const int p = inv_perm[r];
-        if ((unsigned)p >= (unsigned)N) continue;
-        const float w = topk_w[r];
+    auto add_row = [&](int p, float w) {
         const uint4* row = ffn_out + (long long)p * units_per_row;
         uint4 v[UNITS_PER_THREAD];
 #pragma unroll
@@ -103,6 +95,32 @@ __global__ __launch_bounds__(256) void combine_token_kernel(const uint4* __restr
                 acc[i][0] = fmaf(w, __uint_as_float(v[i].x), acc[i][0]); acc[i][1] = fmaf(w, __uint_as_float(v[i].y), acc[i][1]);
                 acc[i][2] = fmaf(w, __uint_as_float(v[i].z), acc[i][2]); acc[i][3] = fmaf(w, __uint_as_float(v[i].w), acc[i][3]);
             }
+        }
+    };
+    if (k <= 8 && local_gpu < 0) {
+        // every expert resident: the token's positions and weights are all fetched before any is used
+        // (independent wave-uniform loads instead of a dependent chain per route).  With a resident subset
+        // the chain below is faster: most routes are skipped after two short loads.
+        int p[8];
+        float w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            p[j] = (j < k) ? inv_perm[t * k + j] : -1;
+            w[j] = (j < k) ? topk_w[t * k + j] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if ((unsigned)p[j] < (unsigned)N) add_row(p[j], w[j]);
+    } else {
+        for (int j = 0; j < k; ++j) {
+            const long long r = t * k + j;
+            if (local_gpu >= 0) {
+                const int ex = topk_idx[r];
+                if ((unsigned)ex >= (unsigned)E || placement[ex] != local_gpu) continue;
+            }
+            const int p = inv_perm[r];
+            if ((unsigned)p >= (unsigned)N) continue;
+            add_row(p, topk_w[r]);
         }
     }
 #pragma unroll
