@@ -44,8 +44,9 @@
 // the stage that tile kt+1 overwrites.  The loads are issued from inline
 // assembly: the compiler then does not treat them as LDS writes that every
 // later LDS read must wait for, and the wait is explicit (s_waitcnt vmcnt(0)
-// before the barrier).  They are spread between the matrix instructions, and
-// the LDS fragment reads run one column ahead of the matrix instructions.
+// before the barrier).  They are issued by four of the eight wavefronts (the
+// older one of each SIMD), spread between its matrix instructions, and the LDS
+// fragment reads run one column ahead of the matrix instructions.
 //
 // Tail balancing (down projection).  The tiles of the last, partly filled round
 // on an XCD are each split along k into s parts that run as separate workgroups
@@ -266,21 +267,31 @@ __device__ __forceinline__ int active_blocks(int rows, int wave_m, int fm) {
     return n < 0 ? 0 : (n > fm ? fm : n);
 }
 
-// what a wavefront needs to fetch its share of a k tile: per-lane byte offsets of its 1 KB pieces
-// (the k tile moves the scalar base) and the LDS address of its first piece in stage 0
+// What a loading wavefront needs to fetch its share of a k tile: per-lane byte offsets of its 1 KB
+// pieces (the k tile moves the scalar base) and the LDS address of its first piece in stage 0.
+// Only the first NL wavefronts of a workgroup (one per SIMD, the older of its two) issue the loads.  The
+// SIMD gives its older wavefront the issue slot whenever both are ready, so the younger one runs its
+// matrix instructions late in the k tile; loads placed in its instruction stream start late too, and a
+// wavefront waiting to issue a load holds back its own matrix instructions.  With all twenty pieces of a
+// k tile in the older wavefronts' streams both projections gained 2-3 %; the younger four as loaders
+// lost 10 %, two loaders instead of four 25 %.
+// A loader's activation pieces are 8-row chunks NL * 8 rows apart: their per-lane offsets differ by a
+// constant (the swizzle term of a row depends on the chunk's parity only, which NL = 4 preserves), so one
+// offset register serves all of them; offsets past the bucket's last row are clamped into that row.
+constexpr int NL = 4;
 template <int FM>
 struct Loader {
-    uint32_t a_voff[Tile<FM>::A_PER_WAVE], b_voff[B_PER_WAVE];
+    static constexpr int A_PER_L = Tile<FM>::A_CHUNKS / NL, B_PER_L = B_CHUNKS / NL;
+    uint32_t a_voff0, a_vmax, a_step, b_voff0;
     const uint16_t* Abase;
     const uint16_t* Bbase;
     uint32_t lds;
-    static constexpr int N_DMA = Tile<FM>::A_PER_WAVE + B_PER_WAVE;
-    // piece j of k tile kt: first the activation pieces, then the weight pieces
+    static constexpr int N_DMA = A_PER_L + B_PER_L;
     __device__ __forceinline__ void issue(int j, int kt, int stage) const {
         const uint32_t l = lds + (uint32_t)stage * (Tile<FM>::STAGE * 2);
-        if (j < Tile<FM>::A_PER_WAVE) dma16(a_voff[j], Abase + (size_t)kt * BK, l + j * NW * 1024);
-        else dma16(b_voff[j - Tile<FM>::A_PER_WAVE], Bbase + (size_t)kt * (BK * BN),
-                   l + (Tile<FM>::A_CHUNKS + (j - Tile<FM>::A_PER_WAVE) * NW) * 1024);
+        if (j < A_PER_L) dma16(min(a_voff0 + (uint32_t)j * a_step, a_vmax), Abase + (size_t)kt * BK, l + j * NL * 1024);
+        else dma16(b_voff0, Bbase + (size_t)kt * (BK * BN) + (size_t)(j - A_PER_L) * (NL * 512),
+                   l + (Tile<FM>::A_CHUNKS + (j - A_PER_L) * NL) * 1024);
     }
 };
 
@@ -293,7 +304,7 @@ struct Loader {
 // Fragments are streamed: the weight fragment of the next column is read while the current column
 // multiplies, and each activation fragment of the next 32 k is read into place right after its last
 // use, so that a matrix instruction rarely waits for LDS.  The schedule is pinned.
-template <int FM, int NF>
+template <int FM, int NF, bool LOADER>
 __device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* As, const Loader<FM>& ld, int kt, int stage,
                                       bool load, int wave_m, int wave_n, int lane) {
     constexpr int BM = Tile<FM>::BM, N_DMA = Loader<FM>::N_DMA, NR = 2 * NF;
@@ -304,7 +315,7 @@ __device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* 
     // stage: the stream of matrix instructions then holds no branch at all, which is worth more than the
     // one redundant tile per output tile costs
     const int ktn = load ? kt + 1 : kt;
-    if (UPFRONT > 0) {
+    if (LOADER && UPFRONT > 0) {
 #pragma unroll
         for (int j = 0; j < UPFRONT; ++j) ld.issue(j, ktn, stage ^ 1);
     }
@@ -337,7 +348,7 @@ __device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* 
                 if (b == FN - 1 && ks + 1 < KB) af[a] = read_a(a, ks + 1);
                 const int m = c * NR + a;
                 __builtin_amdgcn_sched_barrier(0);
-                if (m % kDmaEvery == kDmaEvery - 1 && UPFRONT + m / kDmaEvery < N_DMA) {
+                if (LOADER && m % kDmaEvery == kDmaEvery - 1 && UPFRONT + m / kDmaEvery < N_DMA) {
                     ld.issue(UPFRONT + m / kDmaEvery, ktn, stage ^ 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -347,7 +358,7 @@ __device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* 
 }
 
 // the k loop of a wavefront with NF active 32-row blocks (NF = 0: it only fetches its share of the tiles)
-template <int FM, int NF>
+template <int FM, int NF, bool LOADER>
 __device__ __forceinline__ void kloop(f32x4 (&acc)[2 * FM][FN], const uint16_t* smem, const Loader<FM>& ld, const WorkItem& w,
                                       int wave_m, int wave_n, int lane) {
     constexpr int STAGE = Tile<FM>::STAGE, N_DMA = Loader<FM>::N_DMA;
@@ -357,8 +368,8 @@ __device__ __forceinline__ void kloop(f32x4 (&acc)[2 * FM][FN], const uint16_t* 
         __syncthreads();                                     // everyone's have, and tile kt-1 has been consumed
         const bool more = kt + 1 < w.kt1;
         if (NF > 0) {
-            ktile<FM, (NF > 0 ? NF : 1)>(acc, smem + stage * STAGE, ld, kt, stage, more, wave_m, wave_n, lane);
-        } else if (more) {
+            ktile<FM, (NF > 0 ? NF : 1), LOADER>(acc, smem + stage * STAGE, ld, kt, stage, more, wave_m, wave_n, lane);
+        } else if (LOADER && more) {
 #pragma unroll
             for (int j = 0; j < N_DMA; ++j) ld.issue(j, kt + 1, stage ^ 1);
         }
@@ -375,25 +386,30 @@ __device__ __forceinline__ void mainloop(f32x4 (&acc)[2 * FM][FN], uint16_t* sme
     const int wave_m = wave / WN, wave_n = wave % WN;
     Loader<FM> ld;
     ld.Abase = A + (size_t)w.row0 * K;
-    ld.Bbase = Bbase;
-    ld.lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem + (uint32_t)wave * 1024u;
-#pragma unroll
-    for (int j = 0; j < A_PER_WAVE; ++j) {
-        const int c = wave + j * NW;                         // rows 8c .. 8c+7
-        const int r = c * 8 + (lane >> 3);
-        const int g = swz(r, lane & 7);                      // global chunk that lands in LDS slot lane & 7
-        ld.a_voff[j] = (uint32_t)min(r, w.rows - 1) * (uint32_t)K * 2u + (uint32_t)g * 16u;   // rows past the bucket re-read its last row
+    ld.Bbase = Bbase + (size_t)(wave % NL) * 512;
+    ld.lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem + (uint32_t)(wave % NL) * 1024u;
+    {
+        const int r = (wave % NL) * 8 + (lane >> 3);
+        ld.a_voff0 = (uint32_t)r * (uint32_t)K * 2u + (uint32_t)swz(r, lane & 7) * 16u;
+        ld.a_vmax = (uint32_t)(w.rows - 1) * (uint32_t)K * 2u + 112u;   // rows past the bucket re-read the end of its last row
+        ld.a_step = (uint32_t)(NL * 8) * (uint32_t)K * 2u;
+        ld.b_voff0 = (uint32_t)lane * 16u;
     }
+    const bool loader = wave < NL;
+    if (loader) {
 #pragma unroll
-    for (int j = 0; j < B_PER_WAVE; ++j) ld.b_voff[j] = (uint32_t)(wave + j * NW) * 1024u + (uint32_t)lane * 16u;
-
-#pragma unroll
-    for (int j = 0; j < N_DMA; ++j) ld.issue(j, w.kt0, 0);
-    // one copy of the loop per number of active blocks: the accumulators of the others stay zero
-    if (nfrag == FM) kloop<FM, FM>(acc, smem, ld, w, wave_m, wave_n, lane);
-    else if (FM >= 2 && nfrag == FM - 1) kloop<FM, (FM >= 2 ? FM - 1 : 0)>(acc, smem, ld, w, wave_m, wave_n, lane);
-    else if (FM >= 3 && nfrag == FM - 2) kloop<FM, (FM >= 3 ? FM - 2 : 0)>(acc, smem, ld, w, wave_m, wave_n, lane);
-    else kloop<FM, 0>(acc, smem, ld, w, wave_m, wave_n, lane);
+        for (int j = 0; j < N_DMA; ++j) ld.issue(j, w.kt0, 0);
+    }
+#define KLOOP(NFV)                                                              \
+    do {                                                                        \
+        if (loader) kloop<FM, NFV, true>(acc, smem, ld, w, wave_m, wave_n, lane); \
+        else kloop<FM, NFV, false>(acc, smem, ld, w, wave_m, wave_n, lane);       \
+    } while (0)
+    if (nfrag == FM) KLOOP(FM);
+    else if (FM >= 2 && nfrag == FM - 1) KLOOP((FM >= 2 ? FM - 1 : 0));
+    else if (FM >= 3 && nfrag == FM - 2) KLOOP((FM >= 3 ? FM - 2 : 0));
+    else KLOOP(0);
+#undef KLOOP
 }
 
 // Tiles of at most kSmallRows rows (the ragged last tile of a bucket, small buckets): there is next to no
