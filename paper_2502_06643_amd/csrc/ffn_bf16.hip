@@ -6,16 +6,18 @@
 //
 // Work decomposition.  A workgroup of 8 wavefronts (4 along rows x 2 along
 // columns, two wavefronts per SIMD) owns one 256 x 256 output tile of one
-// expert, or 384 x 256 when buckets are large on average; the (expert, row
-// tile) list comes from the device-side plan, so no bucket size ever reaches
-// the host.  Workgroup ids are dealt round-robin to the 8 XCDs by the hardware;
+// expert, or 384 x 256 when the resident buckets are large on average (the
+// host decides when it knows them all, else the device-side plan does and the
+// kernels of the other tile height return at once); the (expert, row tile)
+// list comes from that plan, so no bucket size ever reaches the host.  Workgroup ids are dealt round-robin to the 8 XCDs by the hardware;
 // every XCD owns an eighth of the column tiles of every expert (a weight panel
 // passes through one L2 only, and all XCDs see the same mix of experts) and
 // walks them expert -> chunk of row tiles -> column tile -> row tile:
-// workgroups that share an L2 share weight panels and activation rows.  Within a tile the rows are dealt to the four
-// wavefront rows in blocks of 32, and a wavefront skips the blocks that lie
+// workgroups that share an L2 share weight panels and activation rows.
+// Within a tile the rows are dealt to the four wavefront rows in blocks of 32, and a wavefront skips the blocks that lie
 // past the end of a ragged bucket: such a tile costs ceil(rows / 128) blocks
-// per wavefront, every SIMD staying equally loaded.
+// per wavefront, every SIMD staying equally loaded.  Tiles of at most 128
+// rows (up projection) run a three-stage loop of their own, see mainloop_small.
 //
 // Matrix instruction.  v_mfma_f32_16x16x32_bf16: with both operands coming from
 // registers it accumulates 32 k per pass over a 16 x 16 accumulator, half the
@@ -46,7 +48,9 @@
 // later LDS read must wait for, and the wait is explicit (s_waitcnt vmcnt(0)
 // before the barrier).  They are issued by four of the eight wavefronts (the
 // older one of each SIMD), spread between its matrix instructions, and the LDS
-// fragment reads run one column ahead of the matrix instructions.
+// fragment reads run one column ahead of the matrix instructions.  The k tile
+// holds no branch: after the last k tile the loaders fetch that tile once more
+// into the idle stage instead of skipping the loads.
 //
 // Tail balancing (down projection).  The tiles of the last, partly filled round
 // on an XCD are each split along k into s parts that run as separate workgroups
