@@ -7,9 +7,10 @@
 // Work decomposition.  A workgroup of 8 wavefronts (4 along rows x 2 along
 // columns, two wavefronts per SIMD) owns one 256 x 256 output tile of one
 // expert, or 384 x 256 when the resident buckets are large on average (the
-// host decides when it knows them all, else the device-side plan does and the
-// kernels of the other tile height return at once); the (expert, row tile)
-// list comes from that plan, so no bucket size ever reaches the host.  Workgroup ids are dealt round-robin to the 8 XCDs by the hardware;
+// host decides when it knows them all, else the device-side plan does; one
+// launch holds the code of both heights and branches on the plan's header);
+// the (expert, row tile) list comes from that plan, so no bucket size ever
+// reaches the host.  Workgroup ids are dealt round-robin to the 8 XCDs by the hardware;
 // every XCD owns an eighth of the column tiles of every expert (a weight panel
 // passes through one L2 only, and all XCDs see the same mix of experts) and
 // walks them expert -> chunk of row tiles -> column tile -> row tile:
@@ -551,14 +552,13 @@ constexpr int smem_bytes() {
     return loop_bytes > epilogue_bytes<UP>() ? loop_bytes : epilogue_bytes<UP>();
 }
 
+// one workgroup's tile (or k part of a tile) on row tiles of 128 * FM rows
 template <bool UP, bool SPLIT, int FM>
-__global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ Wp,
-                                                            size_t expert_stride, int K, int npad, uint16_t* __restrict__ C,
-                                                            int ldc, const int32_t* __restrict__ plan, float* __restrict__ partials,
-                                                            int cus_per_xcd, int row_chunk) {
+__device__ __forceinline__ void ffn_tile(uint16_t* smem, const uint16_t* __restrict__ A, const uint16_t* __restrict__ Wp,
+                                         size_t expert_stride, int K, int npad, uint16_t* __restrict__ C, int ldc,
+                                         const int32_t* __restrict__ plan, float* __restrict__ partials, int cus_per_xcd,
+                                         int row_chunk) {
     constexpr int BM = Tile<FM>::BM;
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    if (plan[3] != (FM == 3 ? 0 : 1)) return;            // the plan chose the other tile height
     const int32_t* prefix = plan + (FM == 3 ? kPlanTiles0 : kPlanTiles1);
     const int NT = npad / BN, KT = K / BK;
     const int x = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
@@ -609,25 +609,39 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __re
     epilogue<UP, FM>(acc, smem, C, ldc, w, wave, lane, nfrag);
 }
 
+// One launch serves both tile heights: the plan's header says which one this call uses (the host's
+// choice, or the plan kernel's own when only the device knows the bucket sizes), and every workgroup
+// takes that branch.  Registers and LDS are those of the larger tile either way; one workgroup fits a
+// compute unit with both.
+template <bool UP, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void ffn_bf16_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ Wp,
+                                                            size_t expert_stride, int K, int npad, uint16_t* __restrict__ C,
+                                                            int ldc, const int32_t* __restrict__ plan, float* __restrict__ partials,
+                                                            int cus_per_xcd, int row_chunk) {
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    if (plan[3] == 0) ffn_tile<UP, SPLIT, 3>(smem, A, Wp, expert_stride, K, npad, C, ldc, plan, partials, cus_per_xcd, row_chunk);
+    else ffn_tile<UP, SPLIT, 2>(smem, A, Wp, expert_stride, K, npad, C, ldc, plan, partials, cus_per_xcd, row_chunk);
+}
+
 // adds the k parts of the split tail tiles in part order and writes the tiles; a workgroup handles
-// the j-th 32-row block of every wavefront of one tile
-template <int FM>
+// the j-th 32-row block of every wavefront of one tile (fm = 3 or 2 such blocks, by the plan's tile height)
 __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npad, uint16_t* __restrict__ C, int ldc,
                                                                   const int32_t* __restrict__ plan,
                                                                   const float* __restrict__ partials, int cus_per_xcd, int row_chunk) {
-    constexpr int BM = Tile<FM>::BM;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    if (plan[3] != (FM == 3 ? 0 : 1)) return;
-    const int32_t* prefix = plan + (FM == 3 ? kPlanTiles0 : kPlanTiles1);
+    const bool tall = plan[3] == 0;
+    const int fm = tall ? 3 : 2, BM = 128 * fm;
+    const size_t partial_floats = (size_t)BM * BN;
+    const int32_t* prefix = plan + (tall ? kPlanTiles0 : kPlanTiles1);
     const int NT = npad / BN, KT = K / BK;
-    const int x = blockIdx.x % kXcds, q = (blockIdx.x / kXcds) / FM, j = (blockIdx.x / kXcds) % FM;
+    const int x = blockIdx.x % kXcds, q = (blockIdx.x / kXcds) / fm, j = (blockIdx.x / kXcds) % fm;
     const XcdShare sh = xcd_share(prefix[plan[0]], NT, x, KT, cus_per_xcd, true);
     if (q >= sh.tail) return;
     WorkItem w;
     locate_xcd_tile(plan, prefix, sh, x, sh.full + q, BM, row_chunk, w);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if (j >= active_blocks(w.rows, wave / WN, FM)) return;
+    if (j >= active_blocks(w.rows, wave / WN, fm)) return;
     f32x4 blk[2][FN];
 #pragma unroll
     for (int h = 0; h < 2; ++h)
@@ -636,7 +650,7 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
 #pragma unroll
             for (int v = 0; v < 4; ++v) blk[h][b][v] = 0.f;
     for (int part = 0; part < sh.split; ++part) {
-        const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * 2 * cus_per_xcd + q * sh.split + part) * Tile<FM>::kPartialFloats) + tid;
+        const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * 2 * cus_per_xcd + q * sh.split + part) * partial_floats) + tid;
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -679,45 +693,41 @@ struct FfnCall {
     }
 };
 
-// the two projections on row tiles of 128 * FM rows (FM fragment rows per wavefront); the kernels
-// return at once when the plan chose the other tile height
-template <int FM>
+template <bool UP>
+constexpr int launch_smem() { return smem_bytes<UP, 3>() > smem_bytes<UP, 2>() ? smem_bytes<UP, 3>() : smem_bytes<UP, 2>(); }
+
 static int configure() {
     static bool configured = false;
     int rc;
     if (!configured) {
-        if ((rc = set_smem(&ffn_bf16_kernel<true, false, FM>, smem_bytes<true, FM>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_kernel<false, true, FM>, smem_bytes<false, FM>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_fixup_kernel<FM>, epilogue_bytes<false>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_kernel<true, false>, launch_smem<true>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_kernel<false, true>, launch_smem<false>())) != MOE_OK) return rc;
+        if ((rc = set_smem(&ffn_bf16_fixup_kernel, epilogue_bytes<false>())) != MOE_OK) return rc;
         configured = true;
     }
     return MOE_OK;
 }
 
-template <int FM>
-static int run_up(const FfnCall& c) {
-    int rc = configure<FM>();
-    if (rc != MOE_OK) return rc;
-    const long long grid = c.grid_for(npad13(c.f), Tile<FM>::BM, false);
+// the two projections; bm = the smallest tile height the plan may choose (it sizes the grid)
+static int run_up(const FfnCall& c, int bm) {
+    const long long grid = c.grid_for(npad13(c.f), bm, false);
     if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
-    hipLaunchKernelGGL((ffn_bf16_kernel<true, false, FM>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<true, FM>()), c.s,
+    hipLaunchKernelGGL((ffn_bf16_kernel<true, false>), dim3((unsigned)grid), dim3(kThreads), (launch_smem<true>()), c.s,
                        (const uint16_t*)c.a, (const uint16_t*)c.packed, c.stride, c.d, (int)npad13(c.f), (uint16_t*)c.H, c.f, c.plan,
                        c.partials, c.cpx, c.chunk_up);
     return check_launch("moe_expert_ffn_grouped up launch");
 }
 
-template <int FM>
-static int run_down(const FfnCall& c) {
-    int rc = configure<FM>();
-    if (rc != MOE_OK) return rc;
-    const long long grid = c.grid_for(npad2(c.d), Tile<FM>::BM, true);
+static int run_down(const FfnCall& c, int bm, int fm_max) {
+    const long long grid = c.grid_for(npad2(c.d), bm, true);
     if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: too many tiles for one launch");
     const uint16_t* W2 = (const uint16_t*)c.packed + c.s13;
-    hipLaunchKernelGGL((ffn_bf16_kernel<false, true, FM>), dim3((unsigned)grid), dim3(kThreads), (smem_bytes<false, FM>()), c.s,
+    hipLaunchKernelGGL((ffn_bf16_kernel<false, true>), dim3((unsigned)grid), dim3(kThreads), (launch_smem<false>()), c.s,
                        (const uint16_t*)c.H, W2, c.stride, c.f, (int)npad2(c.d), (uint16_t*)c.out, c.d, c.plan, c.partials, c.cpx,
                        c.chunk_down);
-    if ((rc = check_launch("moe_expert_ffn_grouped down launch")) != MOE_OK) return rc;
-    hipLaunchKernelGGL(ffn_bf16_fixup_kernel<FM>, dim3(kXcds * c.cpx * FM), dim3(kThreads), (epilogue_bytes<false>()), c.s, c.f,
+    int rc = check_launch("moe_expert_ffn_grouped down launch");
+    if (rc != MOE_OK) return rc;
+    hipLaunchKernelGGL(ffn_bf16_fixup_kernel, dim3(kXcds * c.cpx * fm_max), dim3(kThreads), (epilogue_bytes<false>()), c.s, c.f,
                        (int)npad2(c.d), (uint16_t*)c.out, c.d, c.plan, c.partials, c.cpx, c.chunk_down);
     return check_launch("moe_expert_ffn_grouped fix-up launch");
 }
@@ -737,10 +747,11 @@ int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packe
     // Row tiles of 384 move about a sixth fewer bytes per flop than tiles of 256, but waste more on
     // ragged buckets and leave compute units idle when there are few tiles: 384 when the resident buckets
     // hold kLargeBucketRows rows or more on average.  When every row is in a resident bucket the host
-    // knows that average; otherwise only the device does (the plan decides), and the kernels of both tile
-    // heights are launched: those of the height not chosen return at once.
+    // knows that average; otherwise only the device does and the plan decides.  Either way the choice
+    // reaches the kernels through the plan's header.
     const bool every_row_resident = local_gpu < 0 && group_expert == nullptr;
     const int choice = every_row_resident ? ((long long)N >= (long long)kLargeBucketRows * E ? 0 : 1) : -1;
+    if ((rc = configure()) != MOE_OK) return rc;
     rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, Tile<3>::BM, Tile<2>::BM, choice, plan, s);
     if (rc != MOE_OK) return rc;
     FfnCall c;
@@ -751,15 +762,15 @@ int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packe
     c.s13 = npad13(f) * d;
     c.stride = c.s13 + npad2(d) * f;
     c.partials = (float*)((char*)H + round_up((size_t)N * f * 2, 256));     // partial tiles live behind H in the workspace
+    const int bm_grid = choice == 0 ? Tile<3>::BM : Tile<2>::BM;     // the grid covers the shorter tiles unless the host chose the tall ones
+    const int fm_max = choice == 1 ? 2 : 3;
     {
         LaunchTimer timer(MOE_K_FFN_UP, s);
-        if (choice != 1 && (rc = run_up<3>(c)) != MOE_OK) return rc;
-        if (choice != 0 && (rc = run_up<2>(c)) != MOE_OK) return rc;
+        if ((rc = run_up(c, bm_grid)) != MOE_OK) return rc;
     }
     {
         LaunchTimer timer(MOE_K_FFN_DOWN, s);
-        if (choice != 1 && (rc = run_down<3>(c)) != MOE_OK) return rc;
-        if (choice != 0 && (rc = run_down<2>(c)) != MOE_OK) return rc;
+        if ((rc = run_down(c, bm_grid, fm_max)) != MOE_OK) return rc;
     }
     return MOE_OK;
 }
