@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("T,d,f,E,k,G,local", [(64, 256, 512, 8, 2, 1, -1),      # decode-sized: streaming FFN kernels, fused index kernel
-                                               (1500, 256, 320, 8, 2, 4, 1)])    # tiled GEMMs, both tile heights launched, split tail
+                                               (1500, 256, 320, 8, 2, 4, 1)])    # tiled GEMMs, tile height chosen on the device, split tail
 def test_layer_step_replays_from_a_graph(lib, T, d, f, E, k, G, local):
     rng = np.random.default_rng(T)
     x = to_device(synth.normal(T, 0, (T, d), 1.0, "bf16"))
