@@ -44,9 +44,12 @@
 // instructions; the swizzle is applied by choosing which global chunk each lane
 // fetches.  Two LDS stages: the loads of k tile kt+1 are in flight while tile kt
 // is multiplied, and one barrier per k tile both publishes tile kt and retires
-// the stage that tile kt+1 overwrites.  The loads are issued from inline
+// the stage that tile kt+1 overwrites.  With 256-row tiles the 160 KB of LDS
+// hold a third weight stage: the weights (streamed from memory, the
+// long-latency operand) are then fetched two k tiles ahead, the activations
+// one (+4-9 % on every batch size that uses these tiles).  The loads are issued from inline
 // assembly: the compiler then does not treat them as LDS writes that every
-// later LDS read must wait for, and the wait is explicit (s_waitcnt vmcnt(0)
+// later LDS read must wait for, and the wait is explicit (s_waitcnt vmcnt
 // before the barrier).  They are issued by four of the eight wavefronts (the
 // older one of each SIMD), spread between its matrix instructions, and the LDS
 // fragment reads run one column ahead of the matrix instructions.  The k tile
@@ -84,7 +87,12 @@ constexpr int B_PER_WAVE = B_CHUNKS / NW;
 constexpr int kThreads = NW * 64;
 template <int FM> struct Tile {
     static constexpr int WTM = 32 * FM, BM = WM * WTM;
-    static constexpr int STAGE = (BM + BN) * BK;            // elements per stage
+    // LDS of the main loop: NS activation stages, then NSB weight stages.  With 256-row tiles a third weight
+    // stage fits (64 + 96 KB): the weights, which come from memory and are the long-latency operand, are then
+    // fetched two k tiles ahead and the activations one
+    static constexpr int NSB = FM == 2 ? 3 : 2;
+    static constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK;           // elements
+    static constexpr int LOOP_ELEMS = NS * A_STAGE + NSB * B_STAGE;
     static constexpr int A_CHUNKS = BM / 8, A_PER_WAVE = A_CHUNKS / NW;
     static constexpr size_t kPartialFloats = (size_t)BM * BN;
 };
@@ -292,11 +300,15 @@ struct Loader {
     const uint16_t* Bbase;
     uint32_t lds;
     static constexpr int N_DMA = A_PER_L + B_PER_L;
-    __device__ __forceinline__ void issue(int j, int kt, int stage) const {
-        const uint32_t l = lds + (uint32_t)stage * (Tile<FM>::STAGE * 2);
-        if (j < A_PER_L) dma16(min(a_voff0 + (uint32_t)j * a_step, a_vmax), Abase + (size_t)kt * BK, l + j * NL * 1024);
-        else dma16(b_voff0, Bbase + (size_t)kt * (BK * BN) + (size_t)(j - A_PER_L) * (NL * 512),
-                   l + (Tile<FM>::A_CHUNKS + (j - A_PER_L) * NL) * 1024);
+    // piece j of a k tile: an activation piece of tile kta into activation stage sa, or a weight piece of
+    // tile ktb into weight stage sb
+    __device__ __forceinline__ void issue(int j, int kta, int ktb, int sa, int sb) const {
+        if (j < A_PER_L)
+            dma16(min(a_voff0 + (uint32_t)j * a_step, a_vmax), Abase + (size_t)kta * BK,
+                  lds + (uint32_t)sa * (Tile<FM>::A_STAGE * 2) + j * NL * 1024);
+        else
+            dma16(b_voff0, Bbase + (size_t)ktb * (BK * BN) + (size_t)(j - A_PER_L) * (NL * 512),
+                  lds + (uint32_t)(NS * Tile<FM>::A_STAGE * 2) + (uint32_t)sb * (Tile<FM>::B_STAGE * 2) + (j - A_PER_L) * NL * 1024);
     }
 };
 
@@ -310,19 +322,17 @@ struct Loader {
 // multiplies, and each activation fragment of the next 32 k is read into place right after its last
 // use, so that a matrix instruction rarely waits for LDS.  The schedule is pinned.
 template <int FM, int NF, bool LOADER>
-__device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* As, const Loader<FM>& ld, int kt, int stage,
-                                      bool load, int wave_m, int wave_n, int lane) {
-    constexpr int BM = Tile<FM>::BM, N_DMA = Loader<FM>::N_DMA, NR = 2 * NF;
+__device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* As, const uint16_t* Bs, const Loader<FM>& ld,
+                                      int kta, int ktb, int sa, int sb, int wave_m, int wave_n, int lane) {
+    constexpr int N_DMA = Loader<FM>::N_DMA, NR = 2 * NF;
     constexpr int SLOTS = KB * NR * FN / kDmaEvery;
     constexpr int UPFRONT = N_DMA > SLOTS ? N_DMA - SLOTS : 0;
-    const uint16_t* Bs = As + BM * BK;
-    // Without `load` (the last k tile) the pieces of this same tile are fetched once more into the idle
-    // stage: the stream of matrix instructions then holds no branch at all, which is worth more than the
-    // one redundant tile per output tile costs
-    const int ktn = load ? kt + 1 : kt;
+    // kta / ktb are the k tiles to fetch (into stages sa / sb), clamped to the last one: near the end the
+    // last tile is fetched again into an idle stage, so the stream of matrix instructions holds no branch at
+    // all, which is worth more than the redundant pieces cost
     if (LOADER && UPFRONT > 0) {
 #pragma unroll
-        for (int j = 0; j < UPFRONT; ++j) ld.issue(j, ktn, stage ^ 1);
+        for (int j = 0; j < UPFRONT; ++j) ld.issue(j, kta, ktb, sa, sb);
     }
     // A operand: lane l holds row l % 16 and the 8 consecutive k that start at 8 * (l / 16)
     auto read_a = [&](int a, int ks) {
@@ -354,7 +364,7 @@ __device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* 
                 const int m = c * NR + a;
                 __builtin_amdgcn_sched_barrier(0);
                 if (LOADER && m % kDmaEvery == kDmaEvery - 1 && UPFRONT + m / kDmaEvery < N_DMA) {
-                    ld.issue(UPFRONT + m / kDmaEvery, ktn, stage ^ 1);
+                    ld.issue(UPFRONT + m / kDmaEvery, kta, ktb, sa, sb);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -366,19 +376,28 @@ __device__ __forceinline__ void ktile(f32x4 (&acc)[2 * FM][FN], const uint16_t* 
 template <int FM, int NF, bool LOADER>
 __device__ __forceinline__ void kloop(f32x4 (&acc)[2 * FM][FN], const uint16_t* smem, const Loader<FM>& ld, const WorkItem& w,
                                       int wave_m, int wave_n, int lane) {
-    constexpr int STAGE = Tile<FM>::STAGE, N_DMA = Loader<FM>::N_DMA;
-    int stage = 0;
+    constexpr int NSB = Tile<FM>::NSB, A_STAGE = Tile<FM>::A_STAGE, B_STAGE = Tile<FM>::B_STAGE, N_DMA = Loader<FM>::N_DMA;
+    static_assert(Loader<FM>::B_PER_L == 8, "the wait below leaves eight weight pieces in flight");
+    const uint16_t* smem_b = smem + NS * A_STAGE;
+    const int last = w.kt1 - 1;
+    int sa = 0, sb = 0;
     for (int kt = w.kt0; kt < w.kt1; ++kt) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wavefront's pieces of tile kt have landed
+        // this wavefront's pieces of tile kt have landed; with three weight stages its (in-order) weight
+        // pieces of tile kt+1, issued last, may still be in flight
+        if (NSB == 3) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();                                     // everyone's have, and tile kt-1 has been consumed
-        const bool more = kt + 1 < w.kt1;
+        const int kta = min(kt + 1, last), ktb = min(kt + NSB - 1, last);
+        const int sa_next = sa ^ 1, sb_next = sb == 0 ? NSB - 1 : sb - 1;      // (sb + NSB - 1) % NSB: the stage of tile kt-1
         if (NF > 0) {
-            ktile<FM, (NF > 0 ? NF : 1), LOADER>(acc, smem + stage * STAGE, ld, kt, stage, more, wave_m, wave_n, lane);
-        } else if (LOADER && more) {
+            ktile<FM, (NF > 0 ? NF : 1), LOADER>(acc, smem + sa * A_STAGE, smem_b + sb * B_STAGE, ld, kta, ktb, sa_next, sb_next,
+                                                 wave_m, wave_n, lane);
+        } else if (LOADER) {
 #pragma unroll
-            for (int j = 0; j < N_DMA; ++j) ld.issue(j, kt + 1, stage ^ 1);
+            for (int j = 0; j < N_DMA; ++j) ld.issue(j, kta, ktb, sa_next, sb_next);
         }
-        stage ^= 1;
+        sa = sa_next;
+        sb = sb + 1 == NSB ? 0 : sb + 1;
     }
 }
 
@@ -403,7 +422,11 @@ __device__ __forceinline__ void mainloop(f32x4 (&acc)[2 * FM][FN], uint16_t* sme
     const bool loader = wave < NL;
     if (loader) {
 #pragma unroll
-        for (int j = 0; j < N_DMA; ++j) ld.issue(j, w.kt0, 0);
+        for (int j = 0; j < N_DMA; ++j) ld.issue(j, w.kt0, w.kt0, 0, 0);
+        if (Tile<FM>::NSB == 3) {
+#pragma unroll
+            for (int j = Loader<FM>::A_PER_L; j < N_DMA; ++j) ld.issue(j, w.kt0, min(w.kt0 + 1, w.kt1 - 1), 0, 1);
+        }
     }
 #define KLOOP(NFV)                                                              \
     do {                                                                        \
@@ -547,7 +570,7 @@ constexpr int epilogue_bytes() { return NW * 32 * ((UP ? WTN / 2 : WTN) + 8) * 2
 
 template <bool UP, int FM>
 constexpr int smem_bytes() {
-    constexpr int stage_bytes = NS * Tile<FM>::STAGE * 2, small_bytes = kSmallStages * kSmallStage * 2;
+    constexpr int stage_bytes = Tile<FM>::LOOP_ELEMS * 2, small_bytes = kSmallStages * kSmallStage * 2;
     constexpr int loop_bytes = stage_bytes > small_bytes ? stage_bytes : small_bytes;
     return loop_bytes > epilogue_bytes<UP>() ? loop_bytes : epilogue_bytes<UP>();
 }
@@ -590,8 +613,16 @@ __device__ __forceinline__ void ffn_tile(uint16_t* smem, const uint16_t* __restr
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc[a][b][v] = 0.f;
 
-    if (UP && w.rows <= kSmallRows) mainloop_small<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag > 0);
-    else mainloop<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag);
+    if (UP && w.rows <= kSmallRows) {
+        mainloop_small<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag > 0);
+    } else if (UP && FM == 3 && w.rows <= Tile<2>::BM) {
+        // a ragged tile of at most 256 rows: no wavefront has a third block, so it runs the loop of the
+        // 256-row tiles (same row dealing) with its third weight stage and without the clamped loads of
+        // the missing rows (up projection only, like the small tiles: the down projection lost 1.5 % with it)
+        mainloop<2>(reinterpret_cast<f32x4(&)[4][FN]>(acc), smem, A, Bbase, K, w, wave, lane, nfrag);
+    } else {
+        mainloop<FM>(acc, smem, A, Bbase, K, w, wave, lane, nfrag);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the pieces fetched during the last k tile land in LDS: nothing may follow them there
 
     if (SPLIT && w.partial >= 0) {

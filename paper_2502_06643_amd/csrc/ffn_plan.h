@@ -29,7 +29,7 @@ static_assert(kPlanInts * sizeof(int32_t) <= kPlanBytes, "plan area too small");
 // local_gpu < 0.
 // choice: 0 or 1 fixes header [3]; -1 lets the device decide from the listed buckets: bm0 when they hold
 // at least kLargeBucketRows rows on average, else bm1.
-constexpr int kLargeBucketRows = 768;
+constexpr int kLargeBucketRows = 544;     // measured crossover at the Mixtral shape: 512 rows per bucket favour 256-row tiles by 1 %, 640 favour 384 by 5 %
 int launch_ffn_plan(const int32_t* counts, const int32_t* starts, const int32_t* placement, int local_gpu,
                     const int32_t* group_expert, int n_weights, int E, int N, int bm0, int bm1, int choice, int32_t* plan,
                     hipStream_t s);
