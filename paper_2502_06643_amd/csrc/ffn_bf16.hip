@@ -100,6 +100,7 @@ constexpr int kPanelCols = 16;
 constexpr int kXcds = 8;
 constexpr int kMaxSplit = 8;
 constexpr int kMinSplitKT = 8;                  // a k part is at least this many k tiles
+constexpr int kMinSplitGain = 16;               // k tiles of time a split tail must save to be worth its fix-up
 constexpr size_t kMaxPartialFloats = (size_t)384 * BN;          // one fp32 partial tile of the largest tile
 
 static inline size_t npad13(int f) { return round_up((size_t)2 * f, BN); }
@@ -211,7 +212,9 @@ __device__ __forceinline__ XcdShare xcd_share(int MT, int NT, int x, int KT, int
                 const int rounds = (r * sp + cus_per_xcd - 1) / cus_per_xcd;
                 if (rounds * best_den < best_num * sp) { best = sp; best_num = rounds; best_den = sp; }
             }
-            if (best > 1 && 4 * best_num <= 3 * best_den) {
+            // ... and saves at least kMinSplitGain k tiles of time: the partial tiles and the fix-up launch cost
+            // about that much, so short reductions (the many-expert layer: 22 k tiles) run their tail whole
+            if (best > 1 && 4 * best_num <= 3 * best_den && (best_den - best_num) * KT >= kMinSplitGain * best_den) {
                 s.full = (int)cnt - r;
                 s.tail = r;
                 s.split = best;
