@@ -62,15 +62,23 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
     y[u] = o;
 }
 
-// Wide rows: one workgroup per token.  The token's k routes (expert, sorted position, weight) are
-// wave-uniform, so they are read once with scalar loads, and every thread then has its k row
-// gathers in flight at the same time.
-template <bool BF16, int UNITS_PER_THREAD>
+// Wide rows: one workgroup per token (four tokens per workgroup, one per wavefront, when a row is at most
+// 4 KB).  The token's k routes (expert, sorted position, weight) are wave-uniform, so they are read once with
+// scalar loads, and every thread then has its k row gathers in flight at the same time.
+template <bool BF16, int UNITS_PER_THREAD, int TOKENS_PER_GROUP>
 __global__ __launch_bounds__(256) void combine_token_kernel(const uint4* __restrict__ ffn_out, const int32_t* __restrict__ inv_perm,
                                                             const int32_t* __restrict__ topk_idx, const float* __restrict__ topk_w,
                                                             const int32_t* __restrict__ placement, int local_gpu,
-                                                            int units_per_row, int E, int k, int N, uint4* __restrict__ y) {
-    const long long t = blockIdx.x;
+                                                            int units_per_row, int E, int k, int N, int T,
+                                                            uint4* __restrict__ y) {
+    // TOKENS_PER_GROUP tokens per workgroup, each on 256 / TOKENS_PER_GROUP threads (whole wavefronts, so the
+    // token stays wave-uniform): short rows would otherwise make workgroups of one 4 KB row each, and the
+    // rate at which workgroups start then bounds the kernel
+    constexpr int TPT = 256 / TOKENS_PER_GROUP;
+    static_assert(TPT % 64 == 0, "a token owns whole wavefronts");
+    const long long t = (long long)blockIdx.x * TOKENS_PER_GROUP + __builtin_amdgcn_readfirstlane(threadIdx.x / TPT);
+    if (t >= T) return;
+    const int c0 = threadIdx.x % TPT;
     float acc[UNITS_PER_THREAD][8];
 #pragma unroll
     for (int i = 0; i < UNITS_PER_THREAD; ++i)
@@ -81,7 +89,7 @@ __global__ __launch_bounds__(256) void combine_token_kernel(const uint4* __restr
         uint4 v[UNITS_PER_THREAD];
 #pragma unroll
         for (int i = 0; i < UNITS_PER_THREAD; ++i) {
-            const int c = threadIdx.x + i * 256;
+            const int c = c0 + i * TPT;
             v[i] = (c < units_per_row) ? row[c] : make_uint4(0u, 0u, 0u, 0u);
         }
 #pragma unroll
@@ -111,6 +119,22 @@ __global__ __launch_bounds__(256) void combine_token_kernel(const uint4* __restr
 #pragma unroll
         for (int j = 0; j < 8; ++j)
             if ((unsigned)p[j] < (unsigned)N) add_row(p[j], w[j]);
+    } else if (k <= 8) {
+        // a resident subset of the experts: the token's k expert ids, then their k owners, are fetched as
+        // two rounds of independent wave-uniform loads; only the routes that turn out to be local (one in
+        // G on average) go on to their position, weight and row
+        int ex[8], owner[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ex[j] = (j < k) ? topk_idx[t * k + j] : -1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) owner[j] = ((unsigned)ex[j] < (unsigned)E) ? placement[ex[j]] : -1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (j >= k || owner[j] != local_gpu) continue;
+            const int p = inv_perm[t * k + j];
+            if ((unsigned)p >= (unsigned)N) continue;
+            add_row(p, topk_w[t * k + j]);
+        }
     } else {
         for (int j = 0; j < k; ++j) {
             const long long r = t * k + j;
@@ -125,7 +149,7 @@ __global__ __launch_bounds__(256) void combine_token_kernel(const uint4* __restr
     }
 #pragma unroll
     for (int i = 0; i < UNITS_PER_THREAD; ++i) {
-        const int c = threadIdx.x + i * 256;
+        const int c = c0 + i * TPT;
         if (c >= units_per_row) break;
         uint4 o;
         if (BF16) {
@@ -148,15 +172,16 @@ int launch_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm,
     if (grid > 0x7FFFFFFFll) return fail(MOE_ERR_UNSUPPORTED, "moe_combine: T*d too large for one launch");
     LaunchTimer timer(MOE_K_COMBINE, s);
     const bool bf = dt == MOE_BF16;
-#define MOE_LAUNCH_TOKEN(BF, UPT)                                                                                   \
-    hipLaunchKernelGGL((combine_token_kernel<BF, UPT>), dim3((unsigned)T), dim3(256), 0, s, (const uint4*)ffn_out, \
-                       inv_perm, topk_idx, topk_w, placement, local_gpu, units_per_row, E, k, T * k, (uint4*)y)
+#define MOE_LAUNCH_TOKEN(BF, UPT, TPG)                                                                                  \
+    hipLaunchKernelGGL((combine_token_kernel<BF, UPT, TPG>), dim3((unsigned)((T + TPG - 1) / TPG)), dim3(256), 0, s,      \
+                       (const uint4*)ffn_out, inv_perm, topk_idx, topk_w, placement, local_gpu, units_per_row, E, k, T * k, T, \
+                       (uint4*)y)
     if (units_per_row >= 192 && units_per_row <= 256) {
-        if (bf) MOE_LAUNCH_TOKEN(true, 1); else MOE_LAUNCH_TOKEN(false, 1);
+        if (bf) MOE_LAUNCH_TOKEN(true, 4, 4); else MOE_LAUNCH_TOKEN(false, 4, 4);
     } else if (units_per_row > 256 && units_per_row <= 512) {
-        if (bf) MOE_LAUNCH_TOKEN(true, 2); else MOE_LAUNCH_TOKEN(false, 2);
+        if (bf) MOE_LAUNCH_TOKEN(true, 2, 1); else MOE_LAUNCH_TOKEN(false, 2, 1);
     } else if (units_per_row > 512 && units_per_row <= 1024) {
-        if (bf) MOE_LAUNCH_TOKEN(true, 4); else MOE_LAUNCH_TOKEN(false, 4);
+        if (bf) MOE_LAUNCH_TOKEN(true, 4, 1); else MOE_LAUNCH_TOKEN(false, 4, 1);
     } else if (bf) {
         hipLaunchKernelGGL(combine_kernel<true>, dim3((unsigned)grid), dim3(256), 0, s, (const uint4*)ffn_out, inv_perm, topk_idx,
                            topk_w, placement, local_gpu, total_units, units_per_row, E, k, T * k, (uint4*)y);
