@@ -112,9 +112,13 @@ def test_ffn_with_the_maximum_number_of_experts(lib):
     assert np.all(got[~loc] == 7.0)
 
 
+# row sizes: 0.5 KB (one thread per 16-byte unit), 4 KB (four tokens per workgroup; 777 tokens leave the last
+# workgroup one token), 8 KB and 16 KB (one workgroup per token, two and four units per thread)
+@pytest.mark.parametrize("d_bytes", [512, 4096, 8192, 16384])
 @pytest.mark.parametrize("dtype,local", [("f32", -1), ("f32", 1), ("bf16", -1), ("bf16", 2)])
-def test_combine_matches_oracle(lib, dtype, local):
-    T, d, E, k, G = 777, 256, 8, 3, 4
+def test_combine_matches_oracle(lib, dtype, local, d_bytes):
+    T, E, k, G = 777, 8, 3, 4
+    d = d_bytes // (2 if dtype == "bf16" else 4)
     rng = np.random.default_rng(3)
     idx = synth.random_topk_idx(3, T, E, k)
     pl = synth.placement_from_sizes((1, 1, 2, 4), seed=3)
