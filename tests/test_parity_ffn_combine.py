@@ -72,6 +72,36 @@ def test_ffn_matches_oracle(lib, dtype, T, d, f, E, k, G, local):
     assert np.all(got[~is_local] == 7.0)
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_ffn_random_shapes_and_routings(lib, seed):
+    """25 seeded random bf16 problems per seed: sizes from a handful of rows to several thousand, 1-64 experts,
+    uniform to heavily skewed routing, every expert resident or a random subset.  Together they reach every
+    path of the grouped GEMM (decode kernels, both tile heights, small tiles, split tails)."""
+    rng = np.random.default_rng(seed)
+    for case in range(25):
+        E = int(rng.choice([1, 2, 3, 4, 8, 16, 64]))
+        k = int(rng.integers(1, min(E, 6) + 1))
+        G = int(rng.choice([g for g in (1, 2, 4, 8) if g <= E]))
+        local = -1 if G == 1 or rng.random() < 0.4 else int(rng.integers(0, G))
+        d, f = 64 * int(rng.integers(1, 17)), 64 * int(rng.integers(1, 33))
+        T = max(1, int(rng.choice([30, 90, 200, 500, 1100, 2300, 4000, 6000])) // k)
+        x, w1, w3, w2, _, _ = make_problem(1000 * seed + case, T, d, f, E, k, G, "bf16")
+        p = 1.0 / np.arange(1, E + 1) ** float(rng.choice([0.0, 1.0, 2.0]))
+        idx = np.stack([rng.choice(E, size=k, replace=False, p=p / p.sum()) for _ in range(T)]).astype(np.int32)
+        pl = rng.permutation(np.arange(E) % G).astype(np.int32)
+        print(f"case {case}: T={T} d={d} f={f} E={E} k={k} G={G} local={local}", flush=True)
+        L = gpu_ffn(lib, x, w1, w3, w2, idx, pl, G, local, "bf16")
+        dsp = O.dispatch(x, idx, pl, G)
+        ref = O.expert_ffn_grouped(dsp["send_buf"], w1, w3, w2, dsp["expert_counts"], dsp["expert_start"], pl, local)
+        got = as_f64(to_host(L.ffn_out))
+        e_sorted = idx.reshape(-1)[dsp["perm"]]
+        is_local = np.ones(len(e_sorted), dtype=bool) if local < 0 else (pl[e_sorted] == local)
+        if is_local.any():
+            assert rel_err(got[is_local], ref[is_local]) <= TOL_BF16, case
+            assert fro_err(got[is_local], ref[is_local]) <= TOL_BF16, case
+        assert np.all(got[~is_local] == 7.0), case
+
+
 def test_ffn_skewed_buckets_including_empty_and_single_row_experts(lib):
     T, d, f, E, k = 600, 128, 256, 8, 1
     x, w1, w3, w2, _, pl = make_problem(5, T, d, f, E, k, 1, "bf16")
