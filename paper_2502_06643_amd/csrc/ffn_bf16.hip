@@ -697,14 +697,13 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
 }
 
 static int cus_per_xcd() {
-    static int cached = 0;
-    if (cached == 0) {
+    // initialised once, thread-safe (function-local static)
+    static const int cached = [] {
         int dev = 0, cus = 0;
         if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= kXcds)
-            cached = cus / kXcds < kMaxCusPerXcd ? cus / kXcds : kMaxCusPerXcd;
-        else
-            cached = 32;
-    }
+            return cus / kXcds < kMaxCusPerXcd ? cus / kXcds : kMaxCusPerXcd;
+        return 32;
+    }();
     return cached;
 }
 
@@ -731,15 +730,14 @@ template <bool UP>
 constexpr int launch_smem() { return smem_bytes<UP, 3>() > smem_bytes<UP, 2>() ? smem_bytes<UP, 3>() : smem_bytes<UP, 2>(); }
 
 static int configure() {
-    static bool configured = false;
-    int rc;
-    if (!configured) {
-        if ((rc = set_smem(&ffn_bf16_kernel<true, false>, launch_smem<true>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_kernel<false, true>, launch_smem<false>())) != MOE_OK) return rc;
-        if ((rc = set_smem(&ffn_bf16_fixup_kernel, epilogue_bytes<false>())) != MOE_OK) return rc;
-        configured = true;
-    }
-    return MOE_OK;
+    // the LDS sizes of the three kernels are raised once per process, thread-safe (function-local static)
+    static const int rc = [] {
+        int r;
+        if ((r = set_smem(&ffn_bf16_kernel<true, false>, launch_smem<true>())) != MOE_OK) return r;
+        if ((r = set_smem(&ffn_bf16_kernel<false, true>, launch_smem<false>())) != MOE_OK) return r;
+        return set_smem(&ffn_bf16_fixup_kernel, epilogue_bytes<false>());
+    }();
+    return rc;
 }
 
 // the two projections; bm = the smallest tile height the plan may choose (it sizes the grid)
