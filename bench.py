@@ -35,7 +35,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # Bytes that cross the L2 boundary per launch of the dominant kernel (up projection), from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain 1 GiB copy of known size; the summary
 # and the commands are in profiles/bench_c2_rocprofv3.md.  Only known for the default workload.
-MEASURED_TRAFFIC_BYTES = {"c2": 4879.0e6 + 234.9e6}
+MEASURED_TRAFFIC_BYTES = {"c2": 5101.2e6 + 234.9e6}
 
 
 def cpu_baseline(cfg, x, lg, weights, pl, budget_rows=8192):
