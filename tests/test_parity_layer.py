@@ -2,12 +2,15 @@
 plus transition counts) on the benchmark configurations, in the launch
 configuration the benchmark times.
 
-Small configs are compared element by element against the full oracle.  At the
-Mixtral-shaped sizes the fp64 FFN is out of reach, so integer outputs are
-compared in full and float outputs on a seeded sample of bucket rows (first,
-last and random rows of every resident expert) and on the tokens all of whose
-local routes were sampled.
+Every configuration is compared in full: all integer outputs bit for bit, every
+resident row of the expert outputs and every token of y element by element
+against the fp64 oracle (its BLAS-backed FFN finishes the Mixtral-shaped
+prefill batch in seconds), at the stated tolerances, end to end included.  The
+measured errors are printed (run with -s to see them).
 """
+import json
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -62,63 +65,104 @@ def test_tiny_fp32_layer_full_oracle(lib, name, map_kind, local_gpu):
     assert fro_err(L.y.cpu().numpy(), ref["y"]) <= TOL_F32
 
 
-def sample_positions(ref, pl, local_gpu, per_expert, seed):
-    """First, last and random rows of every resident expert's bucket."""
-    rng = np.random.default_rng(seed)
-    pos = []
-    for e in range(len(pl)):
-        if local_gpu >= 0 and pl[e] != local_gpu:
-            continue
-        s, c = int(ref["expert_start"][e]), int(ref["expert_counts"][e])
-        if c == 0:
-            continue
-        pick = {s, s + c - 1}
-        pick.update((s + rng.integers(0, c, min(per_expert, c))).tolist())
-        pos.extend(sorted(pick))
-    return np.array(pos, dtype=np.int64)
+def tensor_rel_err(got, ref):
+    """max |got - ref| / max(|ref|, rms(ref)) with the root-mean-square of the WHOLE tensor as the floor: the
+    metric for batches whose rows are all of one scale (every configuration but the chained one)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref))) or 1.0
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rms)))
 
 
-def check_sampled_layer(cfg, L, x, lg, weights, pl, local_gpu, per_expert=24, seed=0):
+def resident_rows(ref, pl, local_gpu, N):
+    """Sorted positions of the routes whose expert lives on local_gpu."""
+    if local_gpu < 0:
+        return np.arange(N, dtype=np.int64)
+    rows = [np.arange(int(ref["expert_start"][e]), int(ref["expert_start"][e]) + int(ref["expert_counts"][e]))
+            for e in range(len(pl)) if pl[e] == local_gpu]
+    return np.sort(np.concatenate(rows)).astype(np.int64) if rows else np.zeros(0, dtype=np.int64)
+
+
+MEASURED = []        # (label, metric, value) of every float comparison below
+
+
+@pytest.fixture(scope="module", autouse=True)
+def report_measured_errors():
+    """After the module's tests: the table of measured errors, printed, and written as JSON to the file
+    named by MOE_PARITY_REPORT when that variable is set."""
+    yield
+    if not MEASURED:
+        return
+    print("\nmeasured float errors (label | metric | value):")
+    for label, metric, value in MEASURED:
+        print(f"  {label} | {metric} | {value:.3e}")
+    path = os.environ.get("MOE_PARITY_REPORT")
+    if path:
+        with open(path, "w") as fh:
+            json.dump([dict(label=a, metric=b, value=c) for a, b, c in MEASURED], fh, indent=1)
+
+
+def check_full_layer(cfg, L, x, lg, weights, pl, local_gpu, label, same_scale_rows=True, same_scale_tokens=None):
+    """Integer outputs in full; EVERY resident row of ffn_out and EVERY token of y against the fp64 oracle
+    (the fp64 FFN of all 8192 routes of the Mixtral-shaped prefill batch takes a few seconds of BLAS time).
+    same_scale_rows: the rows of ffn_out are all of one scale, so the tensor-wide floor is asserted too.
+    same_scale_tokens (default: same_scale_rows and the gate weights of a token's resident experts sum to
+    one or nearly so, i.e. at most top-2 routing): the same for y.  With 8 of 64 experts resident and top-6
+    routing a token's y is scaled by whatever part of its gate mass is local (anything from 0 to 1, most
+    tokens exact zeros), a small element of a large row is then measured against a floor far below that
+    row's own scale, and the tensor-wide figure is printed but not asserted.
+    Returns the oracle's integer outputs."""
+    if same_scale_tokens is None:
+        same_scale_tokens = same_scale_rows and cfg.k <= 2
     idx, w = O.topk_gate(lg, cfg.k)
     ref = O.dispatch(x, idx, pl, cfg.G)
     ref.update(topk_idx=idx, topk_w=w)
     check_ints(L, ref)
-    # tokens whose every local route is sampled: take tokens first, then add their routes
-    pos = sample_positions(ref, pl, local_gpu, per_expert, seed)
-    rng = np.random.default_rng(seed + 1)
-    tokens = rng.choice(cfg.T, size=min(16, cfg.T), replace=False)
-    tok_routes = (tokens[:, None] * cfg.k + np.arange(cfg.k)[None, :]).reshape(-1)
-    if local_gpu >= 0:
-        tok_routes = tok_routes[pl[idx.reshape(-1)[tok_routes]] == local_gpu]
-    pos = np.unique(np.concatenate([pos, ref["inv_perm"][tok_routes].astype(np.int64)]))
-    o_ref = O.expert_ffn_grouped(ref["send_buf"], *weights, ref["expert_counts"], ref["expert_start"], pl, local_gpu, positions=pos)
-    o_gpu = as_f64(to_host(L.ffn_out[torch.from_numpy(pos).cuda()]))
+    N = cfg.T * cfg.k
     tol = TOL_BF16 if cfg.dtype == "bf16" else TOL_F32
-    assert rel_err(o_gpu, o_ref[pos]) <= tol
-    assert fro_err(o_gpu, o_ref[pos]) <= tol
-    y_gpu = as_f64(to_host(L.y[torch.from_numpy(tokens).cuda()]))
+    rows = resident_rows(ref, pl, local_gpu, N)
+    o_ref = O.expert_ffn_grouped(ref["send_buf"], *weights, ref["expert_counts"], ref["expert_start"], pl, local_gpu)
+    o_bits = to_host(L.ffn_out)
+    o_gpu = as_f64(o_bits)
+
+    def record(metric, value, bound):
+        MEASURED.append((label, metric, value))
+        print(f"{label}: {metric} = {value:.3e} (bound {bound:.0e})", flush=True)
+        assert value <= bound, (label, metric, value)
+
+    if rows.size:
+        record("ffn_out rel_err(row rms)", rel_err(o_gpu[rows], o_ref[rows]), tol)
+        if same_scale_rows:
+            record("ffn_out rel_err(tensor rms)", tensor_rel_err(o_gpu[rows], o_ref[rows]), tol)
+        record("ffn_out fro_err", fro_err(o_gpu[rows], o_ref[rows]), tol)
+    y_gpu = as_f64(to_host(L.y))
     # combine as a stage: same inputs on both sides (the GPU's own expert outputs and fp32 gate weights)
-    o_bits = np.zeros((cfg.T * cfg.k, cfg.d), dtype=np.uint16 if cfg.dtype == "bf16" else np.float32)
-    o_bits[pos] = to_host(L.ffn_out[torch.from_numpy(pos).cuda()])
-    y_stage = O.combine(o_bits, ref["inv_perm"], idx, L.topk_w.cpu().numpy(), pl, local_gpu)[tokens]
-    assert rel_err(y_gpu, y_stage) <= tol
-    # end to end against the all-fp64 layer: two bf16 roundings (expert output, then y) compound, so the
-    # element-wise maximum gets twice the single-stage allowance; the Frobenius error keeps the single one
-    y_ref = O.combine(o_ref, ref["inv_perm"], idx, w, pl, local_gpu)[tokens]
-    assert fro_err(y_gpu, y_ref) <= tol
-    assert rel_err(y_gpu, y_ref) <= 2 * tol
+    if rows.size < N:
+        keep = np.zeros(N, dtype=bool)
+        keep[rows] = True
+        o_bits = np.where(keep[:, None], o_bits, np.zeros((), dtype=o_bits.dtype))
+    y_stage = O.combine(o_bits, ref["inv_perm"], idx, L.topk_w.cpu().numpy(), pl, local_gpu)
+    record("y (combine stage) rel_err(row rms)", rel_err(y_gpu, y_stage), tol)
+    # end to end against the all-fp64 layer, at the same tolerance
+    y_ref = O.combine(o_ref, ref["inv_perm"], idx, w, pl, local_gpu)
+    record("y (end to end) rel_err(row rms)", rel_err(y_gpu, y_ref), tol)
+    if same_scale_rows:
+        record("y (end to end) rel_err(tensor rms)", tensor_rel_err(y_gpu, y_ref), tol if same_scale_tokens else float("inf"))
+    record("y (end to end) fro_err", fro_err(y_gpu, y_ref), tol)
     return ref
 
 
 @pytest.mark.parametrize("name", ["c2", "c2b", "c3", "c4"])
-def test_bf16_configs_full_size_sampled(lib, name):
+def test_bf16_configs_full_size_every_row(lib, name):
     cfg = synth.config(name)
     x = synth.make_x(cfg)
     lg = synth.make_logits(cfg, x)
     weights = synth.make_expert_weights(cfg)
     pl = synth.make_placement(cfg)
     L = run_gpu_layer(cfg, x, lg, weights, pl, cfg.local_gpu)
-    ref = check_sampled_layer(cfg, L, x, lg, weights, pl, cfg.local_gpu)
+    ref = check_full_layer(cfg, L, x, lg, weights, pl, cfg.local_gpu, name)
     share = ref["expert_counts"].max() / ref["expert_counts"].sum()
     print(f"{name}: largest expert holds {share:.3f} of the routes; gpu_counts {ref['gpu_counts'].tolist()}")
 
@@ -127,8 +171,10 @@ def test_c5_chained_layers_and_transition_counts(lib):
     """Four Mixtral-shaped layers.  Router logits of every layer come from the
     seeded layer-0 activations (plus the successor bonus keyed on the previous
     layer's top-1 expert), so both sides see identical logits; activations flow
-    layer to layer on the GPU, and each layer's floats are checked with the
-    GPU's own bf16 input of that layer handed to the oracle (teacher forcing)."""
+    layer to layer on the GPU, and each layer's floats are checked, every row
+    and every token, with the GPU's own bf16 input of that layer handed to the
+    oracle (teacher forcing).  Rows of the later layers differ by orders of
+    magnitude, so only the row-scaled metric is asserted there."""
     cfg = synth.config("c5")
     x0 = synth.make_x(cfg)
     pl = synth.make_placement(cfg)
@@ -144,7 +190,7 @@ def test_c5_chained_layers_and_transition_counts(lib):
         x_host = to_host(x_dev)
         L.forward(x_dev, torch.from_numpy(lg).cuda())
         torch.cuda.synchronize()
-        ref = check_sampled_layer(cfg, L, x_host, lg, weights, pl, cfg.local_gpu, per_expert=6, seed=layer)
+        ref = check_full_layer(cfg, L, x_host, lg, weights, pl, cfg.local_gpu, f"c5 layer {layer}", same_scale_rows=layer == 0)
         if layer > 0:
             R = torch.zeros((cfg.E, cfg.E), dtype=torch.int64, device="cuda")
             lib.moe_transition_counts(prev_idx_dev, L.topk_idx, cfg.T, cfg.k, cfg.k, cfg.E, cfg.E, R)
@@ -159,10 +205,10 @@ def test_c5_chained_layers_and_transition_counts(lib):
 
 
 @pytest.mark.parametrize("tp", [2, 4])
-def test_tensor_parallel_expert_shards_full_size_sampled(lib, tp):
+def test_tensor_parallel_expert_shards_full_size_every_row(lib, tp):
     """Section 4 runs 4EP-2TP and 4EP-4TP: every expert's FFN is cut along f over tp ranks.  One rank's
     share is the same path at f / tp (its slices of W1, W3 and W2); the all-reduce of the partial outputs
-    is not part of this build.  Mixtral shape, EP=4 map, sampled against the oracle like the other configs."""
+    is not part of this build.  Mixtral shape, EP=4 map, every row against the oracle like the other configs."""
     cfg = synth.config("c2b")
     cfg = cfg.with_(f=cfg.f // tp, name=f"c2b_tp{tp}")
     x = synth.make_x(cfg)
@@ -170,7 +216,7 @@ def test_tensor_parallel_expert_shards_full_size_sampled(lib, tp):
     weights = synth.make_expert_weights(cfg)
     pl = synth.make_placement(cfg)
     L = run_gpu_layer(cfg, x, lg, weights, pl, cfg.local_gpu)
-    check_sampled_layer(cfg, L, x, lg, weights, pl, cfg.local_gpu, per_expert=12)
+    check_full_layer(cfg, L, x, lg, weights, pl, cfg.local_gpu, cfg.name)
 
 
 def test_tensor_parallel_shards_add_up_to_the_whole_expert(lib):

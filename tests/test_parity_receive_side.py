@@ -61,7 +61,9 @@ def test_expert_parallel_group_matches_oracle(lib, dtype, G, T_rank, d, f, E, k,
         single = O.moe_layer(xs[r], lgs[r], k, *weights, pl, G, -1)            # all experts resident on one GPU
         y = as_f64(to_host(ys[r]))
         assert fro_err(y, single["y"]) <= tol
-        assert rel_err(y, single["y"]) <= 2 * tol
+        e2e = rel_err(y, single["y"])
+        print(f"receive side {dtype} G={G} rank {r}: y end to end rel_err = {e2e:.3e}")
+        assert e2e <= tol
 
 
 def test_segments_entry_point_edge_cases(lib):
