@@ -182,6 +182,31 @@ int moe_dispatch(const void* x, moe_dtype_t dt, const int32_t* topk_idx,
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * moe_dispatch_noalloc - moe_dispatch for callers that cannot allocate device
+ * memory or carry a workspace around: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs,
+ * kernels and errors as moe_dispatch, minus the workspace: the per-chunk
+ * histograms go to a buffer of moe_dispatch_static_scratch_bytes() (256 KiB)
+ * that is part of the loaded library on every GPU.  The call allocates and
+ * frees nothing.  A problem with moe_dispatch_workspace_bytes(T,E,k) above
+ * that size is rejected with MOE_ERR_WORKSPACE (nothing is enqueued); E = 8
+ * fits for every T*k, E = 64 up to about one million routes.  All calls on one
+ * GPU share the buffer: calls that may overlap there (different streams,
+ * different threads) race - serialise them or use moe_dispatch.  Nothing in
+ * the buffer has to survive or be cleared between calls.  The first call on a
+ * device looks the buffer's address up (a host-side query, no allocation);
+ * make that call before a stream capture begins.
+ * ---------------------------------------------------------------------- */
+size_t moe_dispatch_static_scratch_bytes(void);
+
+int moe_dispatch_noalloc(const void* x, moe_dtype_t dt, const int32_t* topk_idx,
+                         int T, int d, int E, int k,
+                         const int32_t* placement, int G,
+                         void* send_buf, int32_t* perm, int32_t* inv_perm,
+                         int32_t* expert_counts, int32_t* expert_start,
+                         int32_t* gpu_counts, int32_t* gpu_offsets, void* stream);
+
+/* ------------------------------------------------------------------------
  * moe_pack_weights - one-time re-layout of the expert weights into the order
  * the FFN kernels stream them in (off the hot path; run once per layer).
  *

@@ -27,6 +27,7 @@ KERNEL_NAMES = ["gate", "dispatch_count", "dispatch_scan", "dispatch_rank", "dis
 MOE_K_COUNT = len(KERNEL_NAMES)
 
 EXPORTS = ["moe_last_error", "moe_version", "moe_topk_gate", "moe_topk_gate_norm", "moe_router_packed_bytes", "moe_pack_router", "moe_router_gate", "moe_dispatch_workspace_bytes", "moe_dispatch",
+           "moe_dispatch_static_scratch_bytes", "moe_dispatch_noalloc",
            "moe_packed_weights_bytes", "moe_pack_weights", "moe_ffn_workspace_bytes", "moe_expert_ffn_grouped", "moe_expert_ffn_segments",
            "moe_combine", "moe_transition_counts", "moe_transition_counts_pairs", "moe_accumulate_counts", "moe_placement_loads",
            "moe_placement_traffic", "moe_timing_begin", "moe_timing_end"]
@@ -55,6 +56,9 @@ _lib.moe_router_gate.argtypes = [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _v
 _lib.moe_dispatch_workspace_bytes.argtypes = [_i, _i, _i]
 _lib.moe_dispatch_workspace_bytes.restype = _sz
 _lib.moe_dispatch.argtypes = [_vp, _i, _vp, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.moe_dispatch_static_scratch_bytes.argtypes = []
+_lib.moe_dispatch_static_scratch_bytes.restype = _sz
+_lib.moe_dispatch_noalloc.argtypes = [_vp, _i, _vp, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.moe_packed_weights_bytes.argtypes = [_i, _i, _i, _i]
 _lib.moe_packed_weights_bytes.restype = _sz
 _lib.moe_pack_weights.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _sz, _vp]
@@ -146,6 +150,18 @@ def moe_dispatch(x, dt, topk_idx, T, d, E, k, placement, G, send_buf, perm, inv_
     _check(_lib.moe_dispatch(_ptr(x), dt, _ptr(topk_idx), T, d, E, k, _ptr(placement), G, _ptr(send_buf), _ptr(perm),
                              _ptr(inv_perm), _ptr(expert_counts), _ptr(expert_start), _ptr(gpu_counts),
                              _ptr(gpu_offsets), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_dispatch_static_scratch_bytes() -> int:
+    return _lib.moe_dispatch_static_scratch_bytes()
+
+
+def moe_dispatch_noalloc(x, dt, topk_idx, T, d, E, k, placement, G, send_buf, perm, inv_perm, expert_counts,
+                         expert_start, gpu_counts, gpu_offsets):
+    _dev(x, topk_idx, placement, send_buf, perm, inv_perm, expert_counts, expert_start, gpu_counts, gpu_offsets)
+    _check(_lib.moe_dispatch_noalloc(_ptr(x), dt, _ptr(topk_idx), T, d, E, k, _ptr(placement), G, _ptr(send_buf), _ptr(perm),
+                                     _ptr(inv_perm), _ptr(expert_counts), _ptr(expert_start), _ptr(gpu_counts),
+                                     _ptr(gpu_offsets), _stream()))
 
 
 def moe_packed_weights_bytes(E, d, f, dt) -> int:

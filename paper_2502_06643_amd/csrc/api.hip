@@ -155,32 +155,64 @@ size_t moe_dispatch_workspace_bytes(int T, int E, int k) {
     return round_up((size_t)nb * (size_t)E * sizeof(int32_t), 256);
 }
 
+// scalar and pointer checks shared by the two dispatch entry points; sets row_bytes
+static int check_dispatch_args(const char* who, const void* x, moe_dtype_t dt, const int32_t* topk_idx, int T, int d, int E, int k,
+                               const int32_t* placement, int G, const void* send_buf, const int32_t* perm, const int32_t* inv_perm,
+                               const int32_t* expert_counts, const int32_t* expert_start, const int32_t* gpu_counts,
+                               const int32_t* gpu_offsets, int* row_bytes) {
+    REQUIRE(dt == MOE_F32 || dt == MOE_BF16, "%s: unknown dtype %d", who, (int)dt);
+    REQUIRE(T >= 0, "%s: T=%d < 0", who, T);
+    REQUIRE(E >= 1 && E <= MOE_MAX_EXPERTS, "%s: E=%d outside [1,%d]", who, E, MOE_MAX_EXPERTS);
+    REQUIRE(k >= 1 && k <= E && k <= MOE_MAX_TOPK, "%s: k=%d outside [1,min(E=%d,%d)]", who, k, E, MOE_MAX_TOPK);
+    REQUIRE(G >= 1 && G <= MOE_MAX_GPUS, "%s: G=%d outside [1,%d]", who, G, MOE_MAX_GPUS);
+    REQUIRE((long long)T * k < (1ll << 31), "%s: T*k does not fit int32", who);
+    REQUIRE(placement && expert_counts && expert_start && gpu_counts && gpu_offsets, "%s: NULL output or placement", who);
+    REQUIRE(T == 0 || (topk_idx && perm && inv_perm), "%s: NULL index pointer", who);
+    REQUIRE((x == nullptr) == (send_buf == nullptr), "%s: x and send_buf must both be given or both be NULL", who);
+    *row_bytes = 0;
+    if (x) {
+        REQUIRE(d >= 1, "%s: d=%d < 1", who, d);
+        REQUIRE(((long long)d * elt_bytes(dt)) % 16 == 0, "%s: a row (d=%d) must be a multiple of 16 bytes", who, d);
+        REQUIRE(aligned16(x) && aligned16(send_buf), "%s: x/send_buf must be 16-byte aligned", who);
+        *row_bytes = d * elt_bytes(dt);
+    }
+    return MOE_OK;
+}
+
 int moe_dispatch(const void* x, moe_dtype_t dt, const int32_t* topk_idx, int T, int d, int E, int k,
                  const int32_t* placement, int G, void* send_buf, int32_t* perm, int32_t* inv_perm,
                  int32_t* expert_counts, int32_t* expert_start, int32_t* gpu_counts, int32_t* gpu_offsets,
                  void* workspace, size_t workspace_bytes, void* stream) {
-    REQUIRE(dt == MOE_F32 || dt == MOE_BF16, "moe_dispatch: unknown dtype %d", (int)dt);
-    REQUIRE(T >= 0, "moe_dispatch: T=%d < 0", T);
-    REQUIRE(E >= 1 && E <= MOE_MAX_EXPERTS, "moe_dispatch: E=%d outside [1,%d]", E, MOE_MAX_EXPERTS);
-    REQUIRE(k >= 1 && k <= E && k <= MOE_MAX_TOPK, "moe_dispatch: k=%d outside [1,min(E=%d,%d)]", k, E, MOE_MAX_TOPK);
-    REQUIRE(G >= 1 && G <= MOE_MAX_GPUS, "moe_dispatch: G=%d outside [1,%d]", G, MOE_MAX_GPUS);
-    REQUIRE((long long)T * k < (1ll << 31), "moe_dispatch: T*k does not fit int32");
-    REQUIRE(placement && expert_counts && expert_start && gpu_counts && gpu_offsets, "moe_dispatch: NULL output or placement");
-    REQUIRE(T == 0 || (topk_idx && perm && inv_perm), "moe_dispatch: NULL index pointer");
-    REQUIRE((x == nullptr) == (send_buf == nullptr), "moe_dispatch: x and send_buf must both be given or both be NULL");
     int row_bytes = 0;
-    if (x) {
-        REQUIRE(d >= 1, "moe_dispatch: d=%d < 1", d);
-        REQUIRE(((long long)d * elt_bytes(dt)) % 16 == 0, "moe_dispatch: a row (d=%d) must be a multiple of 16 bytes", d);
-        REQUIRE(aligned16(x) && aligned16(send_buf), "moe_dispatch: x/send_buf must be 16-byte aligned");
-        row_bytes = d * elt_bytes(dt);
-    }
+    int rc = check_dispatch_args("moe_dispatch", x, dt, topk_idx, T, d, E, k, placement, G, send_buf, perm, inv_perm, expert_counts,
+                                 expert_start, gpu_counts, gpu_offsets, &row_bytes);
+    if (rc != MOE_OK) return rc;
     REQUIRE(workspace != nullptr, "moe_dispatch: NULL workspace");
     if (workspace_bytes < moe_dispatch_workspace_bytes(T, E, k))
         return fail(MOE_ERR_WORKSPACE, "moe_dispatch: workspace %zu < %zu bytes", workspace_bytes,
                     moe_dispatch_workspace_bytes(T, E, k));
     return launch_dispatch(x, row_bytes, topk_idx, T, E, k, placement, G, send_buf, perm, inv_perm, expert_counts,
                            expert_start, gpu_counts, gpu_offsets, (int32_t*)workspace, (hipStream_t)stream);
+}
+
+size_t moe_dispatch_static_scratch_bytes(void) { return kDispatchStaticScratchBytes; }
+
+int moe_dispatch_noalloc(const void* x, moe_dtype_t dt, const int32_t* topk_idx, int T, int d, int E, int k,
+                         const int32_t* placement, int G, void* send_buf, int32_t* perm, int32_t* inv_perm,
+                         int32_t* expert_counts, int32_t* expert_start, int32_t* gpu_counts, int32_t* gpu_offsets,
+                         void* stream) {
+    int row_bytes = 0;
+    int rc = check_dispatch_args("moe_dispatch_noalloc", x, dt, topk_idx, T, d, E, k, placement, G, send_buf, perm, inv_perm,
+                                 expert_counts, expert_start, gpu_counts, gpu_offsets, &row_bytes);
+    if (rc != MOE_OK) return rc;
+    const size_t need = moe_dispatch_workspace_bytes(T, E, k);
+    if (need > kDispatchStaticScratchBytes)
+        return fail(MOE_ERR_WORKSPACE, "moe_dispatch_noalloc: T=%d, k=%d, E=%d need %zu bytes of scratch, the built-in buffer holds %zu; "
+                    "use moe_dispatch with a caller workspace", T, k, E, need, kDispatchStaticScratchBytes);
+    int32_t* scratch = nullptr;
+    if ((rc = dispatch_static_scratch(&scratch)) != MOE_OK) return rc;
+    return launch_dispatch(x, row_bytes, topk_idx, T, E, k, placement, G, send_buf, perm, inv_perm, expert_counts,
+                           expert_start, gpu_counts, gpu_offsets, scratch, (hipStream_t)stream);
 }
 
 static int check_ffn_shape(const char* who, int E, int d, int f, moe_dtype_t dt) {

@@ -45,6 +45,11 @@ int launch_dispatch(const void* x, int row_bytes, const int32_t* topk_idx, int T
                     int32_t* expert_counts, int32_t* expert_start, int32_t* gpu_counts,
                     int32_t* gpu_offsets, int32_t* block_counts, hipStream_t s);
 
+// moe_dispatch_noalloc: the per-chunk histograms live in a file-scope device array of this many bytes;
+// dispatch_static_scratch returns the current device's copy of it (looked up once per device)
+constexpr size_t kDispatchStaticScratchBytes = (size_t)256 << 10;
+int dispatch_static_scratch(int32_t** scratch);
+
 int launch_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm, const int32_t* topk_idx,
                    const float* topk_w, const int32_t* placement, int local_gpu, int T, int d, int E, int k,
                    void* y, hipStream_t s);

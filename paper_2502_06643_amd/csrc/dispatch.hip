@@ -15,6 +15,7 @@
 //
 // The result does not depend on how workgroups are scheduled: every position
 // is a pure function of the route id.
+#include <mutex>
 #include "common.h"
 
 namespace moe {
@@ -277,6 +278,35 @@ __global__ __launch_bounds__(256) void dispatch_rows_kernel(const uint4* __restr
         const int p = inv_perm[t * k + j];
         if ((unsigned)p < (unsigned)N) send_buf[(long long)p * units_per_row + c] = v;
     }
+}
+
+// Scratch of moe_dispatch_noalloc: the per-chunk expert histograms (count -> scan -> rank) in device memory
+// that exists from the moment the library is loaded, so that the call allocates nothing.  Every GPU the
+// library runs on holds its own copy at its own address; in host code the array's name is only a handle
+// for hipGetSymbolAddress, never a pointer to pass to a kernel.  The count kernel writes every entry the
+// scan and rank kernels read, so nothing has to be cleared between calls; calls that overlap on one GPU
+// share the array and race.
+static __device__ __align__(256) unsigned char dispatch_scratch[kDispatchStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+
+int dispatch_static_scratch(int32_t** scratch) {
+    static std::mutex mu;
+    static void* addr[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "moe_dispatch_noalloc: hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(MOE_ERR_UNSUPPORTED, "moe_dispatch_noalloc: device %d outside [0,%d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(mu);
+    if (addr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(dispatch_scratch));     // this device's copy (dev is current)
+        if (e != hipSuccess) return hip_fail(e, "moe_dispatch_noalloc: hipGetSymbolAddress");
+        if (p == nullptr) return fail(MOE_ERR_HIP, "moe_dispatch_noalloc: no device address for the scratch array");
+        addr[dev] = p;
+    }
+    *scratch = static_cast<int32_t*>(addr[dev]);
+    return MOE_OK;
 }
 
 int launch_dispatch(const void* x, int row_bytes, const int32_t* topk_idx, int T, int E, int k,

@@ -64,6 +64,12 @@ def test_bad_scalars_are_rejected_without_touching_the_gpu():
     assert L.moe_dispatch(None, 0, one, 4, 8, 8, 2, one, 0, None, one, one, one, one, one, one, one, 1 << 20, None) == -1   # G=0
     assert L.moe_dispatch(one, 1, one, 4, 12, 8, 2, one, 4, one, one, one, one, one, one, one, one, 1 << 20, None) == -1    # row not 16B multiple
     assert L.moe_dispatch(None, 1, one, 4000, 8, 8, 2, one, 4, None, one, one, one, one, one, one, one, 16, None) == -3     # workspace
+    # the entry point with built-in scratch: same scalar checks, and sizes beyond its 256 KiB buffer are refused before any GPU call
+    assert L.moe_dispatch_noalloc(None, 0, one, 4, 8, 8, 2, one, 0, None, one, one, one, one, one, one, None) == -1          # G=0
+    assert L.moe_dispatch_static_scratch_bytes() == 256 << 10
+    assert L.moe_dispatch_workspace_bytes(1 << 20, 256, 2) > L.moe_dispatch_static_scratch_bytes()
+    assert L.moe_dispatch_noalloc(None, 1, one, 1 << 20, 8, 256, 2, one, 4, None, one, one, one, one, one, one, None) == -3
+    assert b"moe_dispatch_noalloc" in L.moe_last_error() and b"scratch" in L.moe_last_error()
     assert L.moe_expert_ffn_grouped(one, 1, 8, 100, 256, 8, one, one, one, one, 0, one, one, 1 << 30, None) == -2           # bf16 d%64
     assert L.moe_expert_ffn_grouped(one, 1, 8, 128, 256, 8, one, one, one, one, -2, one, one, 1 << 30, None) == -1
     assert L.moe_expert_ffn_grouped(one, 1, 8, 128, 256, 8, one, one, one, one, 0, one, one, 16, None) == -3
