@@ -267,6 +267,10 @@ __device__ __forceinline__ void locate_xcd_tile(const int32_t* __restrict__ plan
 // ---------------------------------------------------------------------------
 // pieces of the GEMM
 // ---------------------------------------------------------------------------
+// M0 (the LDS destination) is written here without being declared clobbered: the compiler reserves M0, never
+// keeps a value of its own in it across statements and rejects it on a clobber list; it writes M0 itself only
+// right in front of an instruction that reads it implicitly (indirect register indexing, which these kernels
+// avoid: every register-array index is a compile-time constant).
 __device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
                  :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
