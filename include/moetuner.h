@@ -127,13 +127,15 @@ int moe_topk_gate_norm(const float* logits, int T, int E, int k, moe_norm_t norm
 
 /* ------------------------------------------------------------------------
  * moe_router_gate - the linear router in front of the gate (Section 2.1):
- *   logits[t][e] = sum_i x[t][i] * W_g[i][e] + bias[e],   then moe_topk_gate.
+ *   logits[t][e] = sum_i x[t][i] * W_g[i][e] + bias[e],   then moe_topk_gate,
+ * in one kernel: the selection runs on the logits while they are still on the
+ * compute unit.
  *
  *   x        [T,d] dt
  *   packed_router     W_g [d,E] re-laid out once by moe_pack_router (opaque,
  *                     >= moe_router_packed_bytes(d,E,dt) bytes)
  *   bias     [E] float, or NULL
- *   logits   [T,E] float  out (required: the selection reads it back)
+ *   logits   [T,E] float  out, or NULL when the caller does not need them
  *   topk_idx, topk_w      as in moe_topk_gate
  *
  * MOE_BF16: bf16 inputs, fp32 accumulation in a fixed order; requires

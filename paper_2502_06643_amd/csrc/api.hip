@@ -141,7 +141,7 @@ int moe_router_gate(const void* x, moe_dtype_t dt, const void* packed_router, co
     REQUIRE(k >= 1 && k <= E && k <= MOE_MAX_TOPK, "moe_router_gate: k=%d outside [1,min(E=%d,%d)]", k, E, MOE_MAX_TOPK);
     REQUIRE((long long)T * E < (1ll << 31), "moe_router_gate: T*E too large");
     if (T == 0) return MOE_OK;
-    REQUIRE(x && packed_router && logits && topk_idx && topk_w, "moe_router_gate: NULL pointer");
+    REQUIRE(x && packed_router && topk_idx && topk_w, "moe_router_gate: NULL pointer");
     REQUIRE(aligned16(x) && aligned16(packed_router) && aligned16(logits) && aligned16(topk_idx) && aligned16(topk_w),
             "moe_router_gate: pointers must be 16-byte aligned");
     return launch_router_gate(x, dt, packed_router, bias, T, d, E, k, logits, topk_idx, topk_w, (hipStream_t)stream);

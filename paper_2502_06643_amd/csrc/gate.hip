@@ -12,20 +12,9 @@
 // the softmax over all E logits read at the selected experts: then every lane
 // adds exp(logit - top) over its own logits after the first round and a
 // butterfly sum over the L lanes gives the denominator.
-#include "common.h"
+#include "gate_select.h"
 
 namespace moe {
-
-__device__ __forceinline__ uint32_t orderable(float v) {
-    if (v == 0.0f) v = 0.0f;                       // -0.0 and +0.0 tie
-    const uint32_t u = __float_as_uint(v);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-__device__ __forceinline__ float from_orderable(uint32_t o) {
-    const uint32_t u = (o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o;
-    return __uint_as_float(u);
-}
 
 template <int L, int VPL, int KMAX, bool ALL>
 __global__ __launch_bounds__(256) void gate_kernel(const float* __restrict__ logits, int T, int E, int k,
@@ -34,86 +23,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const float* __restrict__ log
     const int sub = threadIdx.x % L;
     const long long t = (long long)blockIdx.x * TOK_PER_BLOCK + threadIdx.x / L;
     const bool live = t < T;
-    const int e0 = sub * VPL;
-
-    uint32_t key[VPL];
-#pragma unroll
-    for (int i = 0; i < VPL; ++i) key[i] = 0u;
-    if (live) {
-        const float* row = logits + t * E;
-        if ((E & 3) == 0) {
-#pragma unroll
-            for (int c = 0; c < VPL / 4; ++c) {
-                if (e0 + 4 * c < E) {
-                    const float4 q = *reinterpret_cast<const float4*>(row + e0 + 4 * c);
-                    key[4 * c] = orderable(q.x); key[4 * c + 1] = orderable(q.y);
-                    key[4 * c + 2] = orderable(q.z); key[4 * c + 3] = orderable(q.w);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < VPL; ++i)
-                if (e0 + i < E) key[i] = orderable(row[e0 + i]);
-        }
-    }
-
-    // KMAX >= k is a compile-time bound so that the selected experts and weights stay in registers
-    // and are written once
-    float top = 0.f, denom = 0.f;
-    float p_sel[KMAX];
-    int e_sel[KMAX];
-#pragma unroll
-    for (int j = 0; j < KMAX; ++j) {
-        p_sel[j] = 0.f;
-        e_sel[j] = 0;
-        if (j < k) {
-            uint32_t best = key[0];
-            int bi = 0;
-#pragma unroll
-            for (int i = 1; i < VPL; ++i)
-                if (key[i] > best) { best = key[i]; bi = i; }
-            int be = e0 + bi;
-#pragma unroll
-            for (int m = 1; m < L; m <<= 1) {
-                const uint32_t ok = __shfl_xor(best, m, 64);
-                const int oe = __shfl_xor(be, m, 64);
-                if (ok > best || (ok == best && oe < be)) { best = ok; be = oe; }
-            }
-            if (ALL && j == 0) {                    // before the winner is retired: every logit still has its key
-                const float t0 = from_orderable(best);
-                float sum = 0.f;
-#pragma unroll
-                for (int i = 0; i < VPL; ++i)
-                    if (key[i] != 0u) sum += expf(from_orderable(key[i]) - t0);
-#pragma unroll
-                for (int m = 1; m < L; m <<= 1) sum += __shfl_xor(sum, m, 64);
-                denom = sum;
-            }
-            const int mine = be - e0;               // in [0,VPL) only for the owner lane
-#pragma unroll
-            for (int i = 0; i < VPL; ++i)
-                if (i == mine) key[i] = 0u;
-            const float lj = from_orderable(best);
-            if (j == 0) top = lj;
-            const float p = expf(lj - top);         // exp(0) = 1 for the top-1 expert
-            if (!ALL) denom += p;
-            p_sel[j] = p;
-            e_sel[j] = be;
-        }
-    }
-    if (live && sub == 0) {
-        if (KMAX == 2 && k == 2) {                  // the common top-2 case: one 8-byte store each
-            *reinterpret_cast<int2*>(topk_idx + t * 2) = make_int2(e_sel[0], e_sel[1]);
-            *reinterpret_cast<float2*>(topk_w + t * 2) = make_float2(p_sel[0] / denom, p_sel[1] / denom);
-        } else {
-#pragma unroll
-            for (int j = 0; j < KMAX; ++j)
-                if (j < k) {
-                    topk_idx[t * k + j] = e_sel[j];
-                    topk_w[t * k + j] = p_sel[j] / denom;
-                }
-        }
-    }
+    gate_select<L, VPL, KMAX, ALL>(logits + (live ? t : 0) * E, false, sub, live, t, E, k, topk_idx, topk_w);
 }
 
 template <int L, int VPL, bool ALL>

@@ -1,4 +1,4 @@
-"""GPU parity: moe_router_gate (x . W_g + bias, then top-k) vs the fp64 oracle.
+"""GPU parity: moe_router_gate (x . W_g + bias and the top-k selection, one kernel) vs the fp64 oracle.
 
 The logits are floating point (fp32 accumulation on the GPU, fp64 in the
 oracle): they must agree within 1e-5 of the row scale.  The selected experts
@@ -18,7 +18,7 @@ from paper_2502_06643_amd.layer import to_device
 pytestmark = pytest.mark.gpu
 
 
-def run_router(lib, x, w_g, bias, k):
+def run_router(lib, x, w_g, bias, k, want_logits=True):
     T, d = x.shape
     E = w_g.shape[1]
     dt = lib.MOE_BF16 if x.dtype == np.uint16 else lib.MOE_F32
@@ -28,7 +28,7 @@ def run_router(lib, x, w_g, bias, k):
     idx = torch.full((T, k), -1, dtype=torch.int32, device="cuda")
     w = torch.full((T, k), -1.0, dtype=torch.float32, device="cuda")
     b = None if bias is None else torch.from_numpy(np.asarray(bias, dtype=np.float32)).cuda()
-    lib.moe_router_gate(to_device(x), dt, packed, b, T, d, E, k, logits, idx, w)
+    lib.moe_router_gate(to_device(x), dt, packed, b, T, d, E, k, logits if want_logits else None, idx, w)
     torch.cuda.synchronize()
     return logits.cpu().numpy(), idx.cpu().numpy(), w.cpu().numpy()
 
@@ -37,6 +37,18 @@ def check(lib, x, w_g, bias, k):
     bias32 = None if bias is None else np.asarray(bias, dtype=np.float32)       # the GPU receives an fp32 bias
     lg_ref, idx_ref, w_ref = O.router_gate(x, w_g, bias32, k)
     lg, idx, w = run_router(lib, x, w_g, bias, k)
+    # the logits are an optional output: without them nothing is written there and the selection is the same
+    lg_none, idx_none, w_none = run_router(lib, x, w_g, bias, k, want_logits=False)
+    assert np.all(lg_none == 7.0)
+    np.testing.assert_array_equal(idx_none, idx)
+    np.testing.assert_array_equal(w_none, w)
+    # the selection is exactly moe_topk_gate's on the logits that were written
+    idx_gate = torch.full(idx.shape, -1, dtype=torch.int32, device="cuda")
+    w_gate = torch.full(w.shape, -1.0, dtype=torch.float32, device="cuda")
+    lib.moe_topk_gate(torch.from_numpy(lg).cuda(), lg.shape[0], lg.shape[1], k, idx_gate, w_gate)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(idx_gate.cpu().numpy(), idx)
+    np.testing.assert_array_equal(w_gate.cpu().numpy(), w)
     T, E = lg_ref.shape
     scale = np.sqrt(np.mean(lg_ref ** 2, axis=1, keepdims=True)) + 1e-30
     err = np.max(np.abs(lg - lg_ref) / np.maximum(np.abs(lg_ref), scale))
