@@ -285,6 +285,41 @@ int moe_expert_ffn_segments(const void* recv_buf, moe_dtype_t dt,
                             void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * moe_receive_segments - the segment table of the buffer GPU `dest` receives
+ * from the first all-to-all (Section 2.2 / Fig. 2b), built on the device from
+ * the ranks' gathered expert counts, for moe_expert_ffn_segments.
+ *
+ * Source rank s sends dest its bucket for dest, sorted by expert, and the
+ * receive buffer is the concatenation of those buckets in source order.  With
+ * e_0 < e_1 < ... the experts that placement maps to dest, segment
+ * s * n_local + i names expert e_i and holds expert_counts_all[s][e_i] rows;
+ * seg_start is the exclusive running sum in that order.
+ *
+ *   expert_counts_all [G,E] int32   row s = expert_counts of source rank s
+ *                                   (what an all-gather of moe_dispatch's
+ *                                   expert_counts yields); negative = 0
+ *   placement         [E]   int32
+ *   seg_expert, seg_counts, seg_start [max_seg] int32   out; entries past the
+ *                                   last segment are empty segments (0 rows)
+ *                                   at the end of the buffer, so max_seg can
+ *                                   be passed on as n_seg
+ *   src_offset        [G+1] int32   out, or NULL: first row of each source's
+ *                                   rows; [G] = rows received in all
+ *   n_seg             [1]   int32   out, or NULL: G * n_local, the number of
+ *                                   segments there are; when it exceeds
+ *                                   max_seg only the first max_seg were
+ *                                   written and the table must not be used
+ *
+ * Requires 1 <= max_seg <= MOE_MAX_EXPERTS (the limit of
+ * moe_expert_ffn_segments), dest in [0,G).  One small kernel; nothing visits
+ * the host.
+ * ---------------------------------------------------------------------- */
+int moe_receive_segments(const int32_t* expert_counts_all, const int32_t* placement,
+                         int E, int G, int dest, int max_seg,
+                         int32_t* seg_expert, int32_t* seg_counts, int32_t* seg_start,
+                         int32_t* src_offset, int32_t* n_seg, void* stream);
+
+/* ------------------------------------------------------------------------
  * moe_combine - un-permute and gate-weight the expert outputs (the step after
  * the second all-to-all of Fig. 2b):
  *

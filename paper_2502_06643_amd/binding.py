@@ -29,7 +29,7 @@ MOE_K_COUNT = len(KERNEL_NAMES)
 EXPORTS = ["moe_last_error", "moe_version", "moe_topk_gate", "moe_topk_gate_norm", "moe_router_packed_bytes", "moe_pack_router", "moe_router_gate", "moe_dispatch_workspace_bytes", "moe_dispatch",
            "moe_dispatch_static_scratch_bytes", "moe_dispatch_noalloc",
            "moe_packed_weights_bytes", "moe_pack_weights", "moe_ffn_workspace_bytes", "moe_expert_ffn_grouped", "moe_expert_ffn_segments",
-           "moe_combine", "moe_transition_counts", "moe_transition_counts_pairs", "moe_accumulate_counts", "moe_placement_loads",
+           "moe_receive_segments", "moe_combine", "moe_transition_counts", "moe_transition_counts_pairs", "moe_accumulate_counts", "moe_placement_loads",
            "moe_placement_traffic", "moe_timing_begin", "moe_timing_end"]
 
 
@@ -66,6 +66,7 @@ _lib.moe_ffn_workspace_bytes.argtypes = [_i, _i, _i, _i, _i]
 _lib.moe_ffn_workspace_bytes.restype = _sz
 _lib.moe_expert_ffn_grouped.argtypes = [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]
 _lib.moe_expert_ffn_segments.argtypes = [_vp, _i, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.moe_receive_segments.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.moe_combine.argtypes = [_vp, _i, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
 _lib.moe_transition_counts.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
 _lib.moe_transition_counts_pairs.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp]
@@ -191,6 +192,13 @@ def moe_expert_ffn_segments(recv_buf, dt, N, d, f, E, packed_weights, n_seg, seg
     _check(_lib.moe_expert_ffn_segments(_ptr(recv_buf), dt, N, d, f, E, _ptr(packed_weights), n_seg, _ptr(seg_expert),
                                         _ptr(seg_counts), _ptr(seg_start), _ptr(ffn_out), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_receive_segments(expert_counts_all, placement, E, G, dest, max_seg, seg_expert, seg_counts, seg_start, src_offset=None,
+                         n_seg=None):
+    _dev(expert_counts_all, placement, seg_expert, seg_counts, seg_start, src_offset, n_seg)
+    _check(_lib.moe_receive_segments(_ptr(expert_counts_all), _ptr(placement), E, G, dest, max_seg, _ptr(seg_expert),
+                                     _ptr(seg_counts), _ptr(seg_start), _ptr(src_offset), _ptr(n_seg), _stream()))
 
 
 def moe_combine(ffn_out, dt, inv_perm, topk_idx, topk_w, placement, local_gpu, T, d, E, k, y):

@@ -297,6 +297,18 @@ int moe_expert_ffn_segments(const void* recv_buf, moe_dtype_t dt, int N, int d, 
                           seg_expert, E, (float*)ffn_out, plan, (float*)H, s);
 }
 
+int moe_receive_segments(const int32_t* expert_counts_all, const int32_t* placement, int E, int G, int dest, int max_seg,
+                         int32_t* seg_expert, int32_t* seg_counts, int32_t* seg_start, int32_t* src_offset, int32_t* n_seg,
+                         void* stream) {
+    REQUIRE(E >= 1 && E <= MOE_MAX_EXPERTS, "moe_receive_segments: E=%d outside [1,%d]", E, MOE_MAX_EXPERTS);
+    REQUIRE(G >= 1 && G <= MOE_MAX_GPUS, "moe_receive_segments: G=%d outside [1,%d]", G, MOE_MAX_GPUS);
+    REQUIRE(dest >= 0 && dest < G, "moe_receive_segments: dest=%d outside [0,G=%d)", dest, G);
+    REQUIRE(max_seg >= 1 && max_seg <= MOE_MAX_EXPERTS, "moe_receive_segments: max_seg=%d outside [1,%d]", max_seg, MOE_MAX_EXPERTS);
+    REQUIRE(expert_counts_all && placement && seg_expert && seg_counts && seg_start, "moe_receive_segments: NULL pointer");
+    return launch_receive_segments(expert_counts_all, placement, E, G, dest, max_seg, seg_expert, seg_counts, seg_start, src_offset,
+                                   n_seg, (hipStream_t)stream);
+}
+
 int moe_combine(const void* ffn_out, moe_dtype_t dt, const int32_t* inv_perm, const int32_t* topk_idx,
                 const float* topk_w, const int32_t* placement, int local_gpu, int T, int d, int E, int k,
                 void* y, void* stream) {

@@ -66,6 +66,10 @@ int launch_placement_loads(const int64_t* P, const int32_t* placement, int E, in
 int launch_placement_traffic(const int64_t* R, const int32_t* pl_l, const int32_t* pl_l1, int E_l, int E_l1, int G, int64_t* C,
                              const double* B, double* max_cost, hipStream_t s);
 
+int launch_receive_segments(const int32_t* counts_all, const int32_t* placement, int E, int G, int dest, int max_seg,
+                            int32_t* seg_expert, int32_t* seg_counts, int32_t* seg_start, int32_t* src_offset, int32_t* n_seg_out,
+                            hipStream_t s);
+
 // FFN: the workspace starts with a small plan area, followed by H [N,f].
 constexpr size_t kPlanBytes = 8192;
 size_t packed_bytes_f32(int E, int d, int f);

@@ -2,11 +2,14 @@
 
 The G ranks run one after the other.  Every rank gates and dispatches its own
 tokens with the library; the two all-to-alls of the layer are replaced by
-device-to-device copies of the buckets (the split sizes travel to the host
-first, as they do for a real all-to-all-v); every rank in turn then acts as
-receiver and runs `moe_expert_ffn_segments` over the (source rank, expert)
-segments it was sent; the results are copied back to the senders' bucket
-positions and every rank combines.  Plumbing only: nothing here computes.
+device-to-device copies of the buckets (their split sizes travel to the host
+first, as they do for a real all-to-all-v, and are used for nothing but the
+copies); every rank in turn then acts as receiver: `moe_receive_segments`
+builds its (source rank, expert) segment table on the device from the ranks'
+stacked expert_counts (an all-gather in a real group) and
+`moe_expert_ffn_segments` runs over it; the results are copied back to the
+senders' bucket positions and every rank combines.  Plumbing only: nothing
+here computes.
 """
 from __future__ import annotations
 
@@ -31,15 +34,7 @@ class ExpertParallelGroup:
         self.n_max = G * T_rank * k
         self.ws = torch.empty(B.moe_ffn_workspace_bytes(self.n_max, d, f, E, self.dt), dtype=torch.uint8, device=device)
         self.device = device
-        self.received = {}        # dest -> dict(recv_buf, seg_expert, seg_counts, seg_start, out), kept for inspection
-
-    def segments_for(self, dest, expert_counts_host):
-        """(source, expert on dest) segments of dest's receive buffer, source-major, expert ascending."""
-        experts = [e for e in range(self.E) if self.placement[e] == dest]
-        seg_expert = np.array(experts * self.G, dtype=np.int32)
-        seg_counts = np.array([expert_counts_host[s][e] for s in range(self.G) for e in experts], dtype=np.int32)
-        seg_start = np.concatenate([[0], np.cumsum(seg_counts)[:-1]]).astype(np.int32) if len(seg_counts) else seg_counts
-        return seg_expert, seg_counts, seg_start
+        self.received = {}        # dest -> dict(recv_buf, segment tables (device tensors), out), kept for inspection
 
     def forward(self, xs, logits):
         """xs[r] [T_rank,d] and logits[r] [T_rank,E] on the device, per rank.  Returns the ranks' y tensors."""
@@ -49,23 +44,29 @@ class ExpertParallelGroup:
         # split sizes of the all-to-alls: to the host, like the sizes handed to an all-to-all-v
         gpu_counts = torch.stack([r.gpu_counts for r in self.ranks]).cpu().numpy()
         gpu_offsets = torch.stack([r.gpu_offsets for r in self.ranks]).cpu().numpy()
-        expert_counts = torch.stack([r.expert_counts for r in self.ranks]).cpu().numpy()
+        counts_all = torch.stack([r.expert_counts for r in self.ranks]).contiguous()      # [G,E], stays on the device
         self.received = {}
         for dest in range(self.G):
             pieces = [self.ranks[s].send_buf[gpu_offsets[s][dest]:gpu_offsets[s][dest] + gpu_counts[s][dest]] for s in range(self.G)]
             recv = torch.cat(pieces, dim=0).contiguous()                       # first all-to-all
-            seg_expert, seg_counts, seg_start = self.segments_for(dest, expert_counts)
+            n_seg = self.G * int((self.placement == dest).sum())              # from the map alone: no bucket size involved
+            i32 = dict(dtype=torch.int32, device=self.device)
+            seg_expert, seg_counts, seg_start = (torch.empty(max(1, n_seg), **i32) for _ in range(3))
+            src_offset, n_seg_dev = torch.empty(self.G + 1, **i32), torch.empty(1, **i32)
             out = torch.zeros_like(recv)
             n_recv = recv.shape[0]
-            if n_recv and len(seg_expert):
-                B.moe_expert_ffn_segments(recv, self.dt, n_recv, self.d, self.f, self.E, self.packed, len(seg_expert),
-                                          to_device(seg_expert, self.device), to_device(seg_counts, self.device),
-                                          to_device(seg_start, self.device), out, self.ws)
+            if n_seg:
+                B.moe_receive_segments(counts_all, self.ranks[0].placement, self.E, self.G, dest, n_seg, seg_expert, seg_counts,
+                                       seg_start, src_offset, n_seg_dev)
+                if n_recv:
+                    B.moe_expert_ffn_segments(recv, self.dt, n_recv, self.d, self.f, self.E, self.packed, n_seg, seg_expert,
+                                              seg_counts, seg_start, out, self.ws)
             src_off = np.concatenate([[0], np.cumsum(gpu_counts[:, dest])])
             for s in range(self.G):                                             # second all-to-all
                 lo, n = gpu_offsets[s][dest], gpu_counts[s][dest]
                 self.ranks[s].ffn_out[lo:lo + n] = out[src_off[s]:src_off[s + 1]]
-            self.received[dest] = dict(recv_buf=recv, seg_expert=seg_expert, seg_counts=seg_counts, seg_start=seg_start, out=out)
+            self.received[dest] = dict(recv_buf=recv, n_seg=n_seg, seg_expert=seg_expert[:n_seg], seg_counts=seg_counts[:n_seg],
+                                       seg_start=seg_start[:n_seg], src_offset=src_offset, n_seg_dev=n_seg_dev, out=out)
         for r in self.ranks:
             r.combine()
         return [r.y for r in self.ranks]

@@ -117,8 +117,12 @@ def zipf_log_bias(E: int, s: float, rank_of_expert=None) -> np.ndarray:
     return -s * np.log(rank) - math.log(z)
 
 
-def router_logits(x, w_g, bias, bonus=None) -> np.ndarray:
-    """fp32( fp64(x) @ fp64(w_g) + bias (+ bonus) ); x [T,d], w_g [d,E]."""
+def synthetic_logits(x, w_g, bias, bonus=None) -> np.ndarray:
+    """The recipe of the synthetic logits handed, bit for bit, to both the GPU
+    path and the oracle: fp32( fp64(x) @ fp64(w_g) + bias (+ bonus) ), x [T,d],
+    w_g [d,E].  An input generator, not the library's router: that is
+    moe_router_gate, and its checker is the oracle's router_logits; neither is
+    tested against this function."""
     z = to_f64(x) @ to_f64(w_g) + np.asarray(bias, dtype=np.float64)[None, :]
     if bonus is not None:
         z = z + bonus
@@ -271,7 +275,7 @@ def make_logits(cfg: MoEConfig, x: np.ndarray, layer: int = 0, prev_top1=None) -
         assert prev_top1 is not None
         succ = successors(cfg.seed(layer - 1), cfg.E)
         bonus = successor_bonus(np.asarray(prev_top1), succ, cfg.E, cfg.bonus)
-    return router_logits(x, w_g, bias, bonus)
+    return synthetic_logits(x, w_g, bias, bonus)
 
 
 def random_topk_idx(seed: int, T: int, E: int, k: int) -> np.ndarray:

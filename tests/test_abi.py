@@ -83,6 +83,9 @@ def test_bad_scalars_are_rejected_without_touching_the_gpu():
     assert L.moe_expert_ffn_segments(None, 1, 8, 128, 256, 8, None, 0, None, None, None, None, None, 0, None) == 0          # no segment: nothing to do
     assert L.moe_topk_gate_norm(one, 4, 8, 2, 5, one, one, None) == -1                                                      # unknown norm
     assert L.moe_transition_counts_pairs(one, one, 4, 2, 2, 8, 8, 3, one, None) == -1                                       # unknown pair mode
+    assert L.moe_receive_segments(one, one, 8, 4, 4, 8, one, one, one, None, None, None) == -1                              # dest outside [0,G)
+    assert L.moe_receive_segments(one, one, 8, 4, 0, 257, one, one, one, None, None, None) == -1                            # more segments than the segment FFN takes
+    assert L.moe_receive_segments(one, one, 8, 4, 0, 8, one, None, one, None, None, None) == -1                             # NULL table
     assert L.moe_timing_begin(1, 0) == -1
     # empty batches are fine and enqueue nothing
     assert L.moe_topk_gate(None, 0, 8, 2, None, None, None) == 0

@@ -48,9 +48,13 @@ def test_expert_parallel_group_matches_oracle(lib, dtype, G, T_rank, d, f, E, k,
         ex = O.exchange_to(dsps, pl, dest)
         got = grp.received[dest]
         np.testing.assert_array_equal(to_host(got["recv_buf"]).reshape(ex["recv_buf"].shape), ex["recv_buf"])
-        np.testing.assert_array_equal(got["seg_expert"], ex["seg_expert"])
-        np.testing.assert_array_equal(got["seg_counts"], ex["seg_counts"])
-        np.testing.assert_array_equal(got["seg_start"], ex["seg_start"])
+        # the segment table was built on the device (moe_receive_segments): bit exact against the oracle's exchange
+        np.testing.assert_array_equal(got["seg_expert"].cpu().numpy(), ex["seg_expert"])
+        np.testing.assert_array_equal(got["seg_counts"].cpu().numpy(), ex["seg_counts"])
+        np.testing.assert_array_equal(got["seg_start"].cpu().numpy(), ex["seg_start"])
+        if got["n_seg"]:
+            assert int(got["n_seg_dev"].cpu()[0]) == len(ex["seg_expert"])
+            np.testing.assert_array_equal(got["src_offset"].cpu().numpy(), ex["src_offset"])
         if len(ex["recv_buf"]) == 0:
             continue
         ref = O.expert_ffn_segments(ex["recv_buf"], *weights, ex["seg_expert"], ex["seg_counts"], ex["seg_start"])
@@ -64,6 +68,42 @@ def test_expert_parallel_group_matches_oracle(lib, dtype, G, T_rank, d, f, E, k,
         e2e = rel_err(y, single["y"])
         print(f"receive side {dtype} G={G} rank {r}: y end to end rel_err = {e2e:.3e}")
         assert e2e <= tol
+
+
+def test_receive_segments_table_edge_cases(lib):
+    """moe_receive_segments against a host loop: uneven map, a destination without experts, negative counts, a table
+    that is larger than needed (padded with empty segments at the end) and one that is too small (n_seg says so)."""
+    G, E = 5, 12
+    rng = np.random.default_rng(9)
+    pl = np.array([0, 3, 3, 1, 0, 3, 4, 4, 3, 0, 1, 3], dtype=np.int32)          # GPU 2 owns nothing
+    counts = rng.integers(0, 50, (G, E)).astype(np.int32)
+    counts[2, 5] = -7                                                            # treated as 0
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    for dest in range(G):
+        experts = [e for e in range(E) if pl[e] == dest]
+        want_e = np.array(experts * G, dtype=np.int32)
+        want_c = np.array([max(0, counts[s, e]) for s in range(G) for e in experts], dtype=np.int32)
+        want_s = np.concatenate([[0], np.cumsum(want_c)[:-1]]).astype(np.int32) if len(want_c) else want_c
+        total = int(want_c.sum())
+        for max_seg in (max(1, len(want_e)), len(want_e) + 3, max(1, len(want_e) - 2)):
+            i32 = dict(dtype=torch.int32, device="cuda")
+            se, sc, ss = (torch.full((max_seg,), -1, **i32) for _ in range(3))
+            off, n = torch.full((G + 1,), -1, **i32), torch.full((1,), -1, **i32)
+            B.moe_receive_segments(dev(counts), dev(pl), E, G, dest, max_seg, se, sc, ss, off, n)
+            torch.cuda.synchronize()
+            assert int(n.cpu()[0]) == len(want_e)
+            m = min(max_seg, len(want_e))
+            np.testing.assert_array_equal(se.cpu().numpy()[:m], want_e[:m])
+            np.testing.assert_array_equal(sc.cpu().numpy()[:m], want_c[:m])
+            np.testing.assert_array_equal(ss.cpu().numpy()[:m], want_s[:m])
+            if max_seg >= len(want_e):
+                assert np.all(sc.cpu().numpy()[m:] == 0) and np.all(ss.cpu().numpy()[m:] == total)
+                per_src = want_c.reshape(G, -1).sum(axis=1) if len(want_c) else np.zeros(G, dtype=np.int64)
+                np.testing.assert_array_equal(off.cpu().numpy(), np.concatenate([[0], np.cumsum(per_src)]))
+    with pytest.raises(B.MoeError):
+        B.moe_receive_segments(dev(counts), dev(pl), E, G, G, 8, se, sc, ss, off, n)          # dest outside [0,G)
+    with pytest.raises(B.MoeError):
+        B.moe_receive_segments(dev(counts), dev(pl), E, G, 0, 257, se, sc, ss, off, n)        # more than the segment FFN takes
 
 
 def test_segments_entry_point_edge_cases(lib):
@@ -118,12 +158,13 @@ def test_mixtral_shape_receiver_sampled(lib):
     got = grp.received[0]
     rng = np.random.default_rng(0)
     pos = []
-    for c, s in zip(got["seg_counts"], got["seg_start"]):
+    seg_expert, seg_counts, seg_start = (got[n].cpu().numpy() for n in ("seg_expert", "seg_counts", "seg_start"))
+    for c, s in zip(seg_counts, seg_start):
         if c:
             pos += [int(s), int(s + c - 1)] + (s + rng.integers(0, c, 6)).tolist()
     pos = np.unique(np.array(pos, dtype=np.int64))
     recv = to_host(got["recv_buf"])
-    ref = O.expert_ffn_segments(recv, *weights, got["seg_expert"], got["seg_counts"], got["seg_start"], positions=pos)
+    ref = O.expert_ffn_segments(recv, *weights, seg_expert, seg_counts, seg_start, positions=pos)
     out = as_f64(to_host(got["out"][torch.from_numpy(pos).cuda()]))
     assert rel_err(out, ref[pos]) <= TOL_BF16
     assert fro_err(out, ref[pos]) <= TOL_BF16
