@@ -16,8 +16,14 @@ divided by that kernel's mean duration, measured with HIP events recorded
 around the kernel inside the library on the stream it runs on, during the same
 timed steps.  `kernels` is a per-kernel breakdown from a second, separately
 timed pass (event pairs around every kernel perturb the stream slightly, so it
-is kept out of `value`).  `cpu_baseline` times the fp64 oracle on the host on a
-bounded sample of the same workload.
+is kept out of `value`); the two GEMMs also report the rate at which they stream
+the touched experts' weights (the bound that matters when buckets are small).
+`scaled` holds the bandwidth-bound kernels (gate, transition histogram, fused
+router+gate, dispatch row copy, combine) at sizes that can be held against the
+HBM roofline, each once warm (one buffer set, cache resident when it fits) and
+once cold (rotating buffer sets larger than the 256 MB Infinity Cache); it is
+kept out of `value` as well.  `cpu_baseline` times the fp64 oracle on the host
+on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -33,9 +39,111 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 # Bytes that cross the L2 boundary per launch of the dominant kernel (up projection), from two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain 1 GiB copy of known size; the summary
-# and the commands are in profiles/bench_c2_rocprofv3.md.  Only known for the default workload.
-MEASURED_TRAFFIC_BYTES = {"c2": 5101.2e6 + 234.9e6}
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain 1 GiB copy of known size.  The figure is
+# not measured here (counters need the profiler): it is read from the tracked summary of that measurement,
+# which names the commit and the commands it came from, and is null for workloads without such a summary.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "ffn_up_l2_traffic.txt")
+
+
+def measured_traffic(workload):
+    """{'bytes': fetch + write bytes per launch, 'commit': ...} from profiles/ffn_up_l2_traffic.txt, or None."""
+    try:
+        rows = [l.split() for l in open(TRAFFIC_SUMMARY) if l.strip() and not l.startswith("#")]
+    except OSError:
+        return None
+    for r in rows:                      # workload commit fetch_bytes write_bytes
+        if len(r) >= 4 and r[0] == workload:
+            return {"bytes": float(r[2]) + float(r[3]), "commit": r[1]}
+    return None
+
+
+def scaled_block(torch, B):
+    """The bandwidth-bound kernels at sizes where a launch moves enough bytes to be measured against HBM
+    (at the configurations' own sizes they are launch-latency bound): algorithmic bytes / mean kernel time
+    (HIP event pairs inside the library) / 8 TB/s.  'warm' repeats the call on ONE set of buffers (sets below
+    256 MB then live in the Infinity Cache), 'cold' rotates over enough sets (at least 4, more than 256 MB in
+    all) that every call finds its inputs in DRAM."""
+    dev = "cuda"
+    i32 = dict(dtype=torch.int32, device=dev)
+
+    def timed(kernel, calls, n_sets, reps=12):
+        out = {}
+        for mode, sets in (("warm", 1), ("cold", n_sets)):
+            for i in range(2 * sets):
+                calls[i % sets]()
+            torch.cuda.synchronize()
+            B.moe_timing_begin(1 << B.KERNEL_NAMES.index(kernel), reps + 4)
+            for i in range(reps):
+                calls[i % sets]()
+            torch.cuda.synchronize()
+            ms, n = B.moe_timing_end()
+            out[mode] = ms[kernel] / max(1, n[kernel])
+        return out
+
+    def entry(alg_bytes, t, n_sets, set_bytes, **shape):
+        e = dict(shape, algorithmic_bytes=alg_bytes, buffer_sets_cold=n_sets, bytes_per_set=set_bytes)
+        for mode in ("warm", "cold"):
+            gbs = alg_bytes / (t[mode] * 1e-3) / 1e9
+            e[mode] = {"ms": round(t[mode], 5), "GBps": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4)}
+        return e
+
+    def n_sets_for(set_bytes):
+        return max(4, -(-(320 << 20) // set_bytes))
+
+    res = {"peak_GBps": PEAK_HBM_GBS, "gate": [], "transition": [], "router_gate": [], "dispatch_rows": [], "combine": []}
+    E, k = 8, 2
+    for T in (1 << 20, 1 << 22):
+        set_bytes = T * E * 4
+        R = n_sets_for(set_bytes)
+        lg = [torch.randn(T, E, device=dev) for _ in range(R)]
+        idx = [torch.empty(T, k, **i32) for _ in range(R)]
+        w = [torch.empty(T, k, device=dev) for _ in range(R)]
+        calls = [(lambda i=i: B.moe_topk_gate(lg[i], T, E, k, idx[i], w[i])) for i in range(R)]
+        res["gate"].append(entry(T * (4 * E + 8 * k), timed("gate", calls, R), R, set_bytes, T=T, E=E, k=k))
+        # the histogram between two routings of the same batch: the indices just produced and a second set
+        for i in range(R):
+            calls[i]()
+        idx2 = [torch.roll(a, 1, 0).contiguous() for a in idx]
+        Rm = torch.zeros(E, E, dtype=torch.int64, device=dev)
+        hcalls = [(lambda i=i: B.moe_transition_counts(idx[i], idx2[i], T, k, k, E, E, Rm)) for i in range(R)]
+        res["transition"].append(entry(T * 8 * k, timed("transition", hcalls, R), R, 2 * T * k * 4, T=T, E=E, k=k))
+        del lg, idx, idx2, w, calls, hcalls
+    d = 4096
+    for T in (16384, 65536):
+        set_bytes = T * d * 2
+        R = n_sets_for(set_bytes)
+        x = [torch.randn(T, d, device=dev, dtype=torch.bfloat16) for _ in range(R)]
+        wg = (torch.randn(d, E, device=dev) / d ** 0.5).bfloat16()
+        packed = torch.empty(B.moe_router_packed_bytes(d, E, B.MOE_BF16), dtype=torch.uint8, device=dev)
+        B.moe_pack_router(wg, d, E, B.MOE_BF16, packed)
+        idx = [torch.empty(T, k, **i32) for _ in range(R)]
+        w = [torch.empty(T, k, device=dev) for _ in range(R)]
+        calls = [(lambda i=i: B.moe_router_gate(x[i], B.MOE_BF16, packed, None, T, d, E, k, None, idx[i], w[i])) for i in range(R)]
+        res["router_gate"].append(entry(T * d * 2 + T * k * 8, timed("router", calls, R), R, set_bytes, T=T, d=d, E=E, k=k))
+        if T != 65536:
+            del x, idx, w, calls
+            continue
+        # dispatch rows and combine at T = 65536: x [T,d] -> send_buf [T k, d] -> y [T,d]
+        N = T * k
+        for i in range(R):
+            calls[i]()
+        pl = torch.zeros(E, **i32)
+        sb = [torch.empty(N, d, device=dev, dtype=torch.bfloat16) for _ in range(R)]
+        perm, inv = [torch.empty(N, **i32) for _ in range(R)], [torch.empty(N, **i32) for _ in range(R)]
+        cnt, start = torch.empty(E, **i32), torch.empty(E, **i32)
+        gc, go = torch.empty(1, **i32), torch.empty(2, **i32)
+        ws = torch.empty(max(256, B.moe_dispatch_workspace_bytes(T, E, k)), dtype=torch.uint8, device=dev)
+        dcalls = [(lambda i=i: B.moe_dispatch(x[i], B.MOE_BF16, idx[i], T, d, E, k, pl, 1, sb[i], perm[i], inv[i], cnt, start, gc, go, ws))
+                  for i in range(R)]
+        t = timed("dispatch_rows", dcalls, R)
+        res["dispatch_rows"].append(entry(T * d * 2 + N * d * 2 + 4 * N, t, R, set_bytes * (1 + k), T=T, d=d, k=k))
+        y = [torch.empty(T, d, device=dev, dtype=torch.bfloat16) for _ in range(R)]
+        ccalls = [(lambda i=i: B.moe_combine(sb[i], B.MOE_BF16, inv[i], idx[i], w[i], pl, -1, T, d, E, k, y[i])) for i in range(R)]
+        t = timed("combine", ccalls, R)
+        res["combine"].append(entry(N * d * 2 + T * d * 2 + 12 * N, t, R, set_bytes * (1 + k), T=T, d=d, k=k))
+        del x, idx, w, sb, y, perm, inv, calls, dcalls, ccalls
+    torch.cuda.empty_cache()
+    return res
 
 
 def cpu_baseline(cfg, x, lg, weights, pl, budget_rows=8192):
@@ -87,6 +195,9 @@ def main():
                     help="override the workload's token count T (scaled shapes for the bandwidth-bound kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--no-scaled", action="store_true",
+                    help="skip the 'scaled' block (gate, histogram, router, dispatch rows and combine at sizes that can be held "
+                         "against the HBM roofline, warm and cold)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy three times, so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE with")
@@ -147,8 +258,12 @@ def main():
     achieved = up_flops / (up_ms * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else 157.3
     roofline = {"bound": "mfma", "kernel": "ffn_up (A.[W1|W3] + SwiGLU)", "achieved": round(achieved, 2), "peak": peak,
-                "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
                 "ms": round(up_ms, 4), "flops_per_launch": up_flops}
+    traffic = measured_traffic(cfg.name)
+    if traffic is not None:
+        roofline["traffic"] = traffic["bytes"]
+        roofline["traffic_source"] = f"profiles/ffn_up_l2_traffic.txt (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, measured on commit {traffic['commit']})"
     if cfg.dtype == "bf16" and cfg.T * cfg.k <= B.FFN_STREAMING_MAX_ROWS:
         # decode-sized batch: the up projection streams every touched expert's W1 and W3 once and is bound by HBM
         touched = int((counts > 0).sum() if cfg.local_gpu < 0 else (counts[pl == cfg.local_gpu] > 0).sum())
@@ -191,6 +306,11 @@ def main():
             "transition": 8 * N,
         }
         alg_flops = {"ffn_up": 4.0 * d * f * n_local, "ffn_down": 2.0 * d * f * n_local}
+        # the grouped GEMMs also stream every touched resident expert's weights once: the second bound, which is the
+        # binding one when buckets are small (decode-sized batches, the many-expert layer)
+        resident = counts if cfg.local_gpu < 0 else counts[pl == cfg.local_gpu]
+        touched_experts = int((resident > 0).sum())
+        weight_bytes = {"ffn_up": touched_experts * 2.0 * d * f * elt, "ffn_down": touched_experts * 1.0 * d * f * elt}
         kern = {}
         for name in B.KERNEL_NAMES:
             if not n_all[name]:
@@ -202,9 +322,16 @@ def main():
                 ent.update(bound="hbm", achieved_GBps=round(gbs, 1), frac=round(gbs / PEAK_HBM_GBS, 4))
             if name in alg_flops:
                 tf = alg_flops[name] / (ms * 1e-3) / 1e12
-                ent.update(bound="mfma", achieved_TFLOPs=round(tf, 1), frac=round(tf / peak, 4))
+                wgbs = weight_bytes[name] / (ms * 1e-3) / 1e9
+                ent.update(bound="mfma", achieved_TFLOPs=round(tf, 1), frac=round(tf / peak, 4),
+                           weight_stream_GBps=round(wgbs, 1), weight_stream_frac=round(wgbs / PEAK_HBM_GBS, 4))
             kern[name] = ent
         out["kernels"] = kern
+
+    if not args.no_scaled:
+        del L, x_dev, lg_dev
+        torch.cuda.empty_cache()
+        out["scaled"] = scaled_block(torch, B)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, x, lg, weights, pl)
