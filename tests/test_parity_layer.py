@@ -16,6 +16,7 @@ import pytest
 import torch
 
 from oracle import moe_oracle as O
+from paper_2502_06643_amd import binding as B
 from paper_2502_06643_amd import synth
 from paper_2502_06643_amd.layer import MoELayer, to_device, to_host
 from util import TOL_BF16, TOL_F32, as_f64, fro_err, rel_err
@@ -113,7 +114,7 @@ def check_full_layer(cfg, L, x, lg, weights, pl, local_gpu, label, same_scale_ro
     routing a token's y is scaled by whatever part of its gate mass is local (anything from 0 to 1, most
     tokens exact zeros), a small element of a large row is then measured against a floor far below that
     row's own scale, and the tensor-wide figure is printed but not asserted.
-    Returns the oracle's integer outputs."""
+    Returns the oracle's integer outputs and its y.  No oracle input comes from the GPU."""
     if same_scale_tokens is None:
         same_scale_tokens = same_scale_rows and cfg.k <= 2
     idx, w = O.topk_gate(lg, cfg.k)
@@ -138,19 +139,24 @@ def check_full_layer(cfg, L, x, lg, weights, pl, local_gpu, label, same_scale_ro
             record("ffn_out rel_err(tensor rms)", tensor_rel_err(o_gpu[rows], o_ref[rows]), tol)
         record("ffn_out fro_err", fro_err(o_gpu[rows], o_ref[rows]), tol)
     y_gpu = as_f64(to_host(L.y))
-    # combine as a stage: same inputs on both sides (the GPU's own expert outputs and fp32 gate weights)
-    if rows.size < N:
-        keep = np.zeros(N, dtype=bool)
-        keep[rows] = True
-        o_bits = np.where(keep[:, None], o_bits, np.zeros((), dtype=o_bits.dtype))
-    y_stage = O.combine(o_bits, ref["inv_perm"], idx, L.topk_w.cpu().numpy(), pl, local_gpu)
-    record("y (combine stage) rel_err(row rms)", rel_err(y_gpu, y_stage), tol)
+    # combine as a stage, on inputs that come from the oracle alone: its expert outputs rounded to the activation
+    # dtype and its gate weights in fp32, uploaded and combined by the library, against the oracle's combine of the same
+    o_in = synth.f32_to_bf16_bits(o_ref.astype(np.float32)) if cfg.dtype == "bf16" else o_ref.astype(np.float32)
+    w_in = w.astype(np.float32)
+    y_stage_dev = torch.empty_like(L.y)
+    B.moe_combine(to_device(o_in), L.dt, torch.from_numpy(ref["inv_perm"]).cuda(), torch.from_numpy(idx).cuda(),
+                  torch.from_numpy(w_in).cuda(), L.placement, local_gpu, cfg.T, cfg.d, cfg.E, cfg.k, y_stage_dev)
+    torch.cuda.synchronize()
+    y_stage = O.combine(o_in, ref["inv_perm"], idx, w_in, pl, local_gpu)
+    record("y (combine stage) rel_err(row rms)", rel_err(as_f64(to_host(y_stage_dev)), y_stage), tol)
+    del y_stage_dev
     # end to end against the all-fp64 layer, at the same tolerance
     y_ref = O.combine(o_ref, ref["inv_perm"], idx, w, pl, local_gpu)
     record("y (end to end) rel_err(row rms)", rel_err(y_gpu, y_ref), tol)
     if same_scale_rows:
         record("y (end to end) rel_err(tensor rms)", tensor_rel_err(y_gpu, y_ref), tol if same_scale_tokens else float("inf"))
     record("y (end to end) fro_err", fro_err(y_gpu, y_ref), tol)
+    ref["y"] = y_ref
     return ref
 
 
@@ -170,25 +176,28 @@ def test_bf16_configs_full_size_every_row(lib, name):
 def test_c5_chained_layers_and_transition_counts(lib):
     """Four Mixtral-shaped layers.  Router logits of every layer come from the
     seeded layer-0 activations (plus the successor bonus keyed on the previous
-    layer's top-1 expert), so both sides see identical logits; activations flow
-    layer to layer on the GPU, and each layer's floats are checked, every row
-    and every token, with the GPU's own bf16 input of that layer handed to the
-    oracle (teacher forcing).  Rows of the later layers differ by orders of
-    magnitude, so only the row-scaled metric is asserted there."""
+    layer's top-1 expert), so both sides see identical logits.  Activations
+    flow down the ORACLE's chain: the input of layer l+1, for the GPU and the
+    oracle alike, is the oracle's y of layer l rounded to bf16 (no residual, no
+    norm: the configuration names none), so no oracle input ever comes from the
+    GPU; every layer's floats are checked on every row and every token.  Rows
+    of the later layers differ by orders of magnitude, so only the row-scaled
+    metric is asserted there.  The GPU's own y of layer l is compared with the
+    same oracle y (the end-to-end check), which bounds what a free-running GPU
+    chain would feed the next layer."""
     cfg = synth.config("c5")
     x0 = synth.make_x(cfg)
     pl = synth.make_placement(cfg)
     L = MoELayer(cfg.T, cfg.d, cfg.f, cfg.E, cfg.k, cfg.G, cfg.local_gpu, cfg.dtype)
     L.set_placement(pl)
-    x_dev = to_device(x0)
+    x_host = x0
     prev_idx_dev, prev_idx_ref, prev_top1 = None, None, None
     affinity = []
     for layer in range(cfg.layers):
         lg = synth.make_logits(cfg, x0, layer, prev_top1)
         weights = synth.make_expert_weights(cfg, layer)
         L.set_weights(*weights)
-        x_host = to_host(x_dev)
-        L.forward(x_dev, torch.from_numpy(lg).cuda())
+        L.forward(to_device(x_host), torch.from_numpy(lg).cuda())
         torch.cuda.synchronize()
         ref = check_full_layer(cfg, L, x_host, lg, weights, pl, cfg.local_gpu, f"c5 layer {layer}", same_scale_rows=layer == 0)
         if layer > 0:
@@ -199,8 +208,8 @@ def test_c5_chained_layers_and_transition_counts(lib):
             succ = synth.successors(cfg.seed(layer - 1), cfg.E)
             affinity.append(float(np.mean([ref["topk_idx"][t, 0] in succ[prev_top1[t]] for t in range(0, cfg.T, 16)])))
         prev_idx_dev, prev_idx_ref, prev_top1 = L.topk_idx.clone(), ref["topk_idx"], ref["topk_idx"][:, 0]
-        x_dev = L.y.clone()
-        del weights
+        x_host = synth.f32_to_bf16_bits(ref["y"].astype(np.float32))        # the oracle's y, rounded: the next layer's input
+        del weights, ref
     print("c5: fraction of tokens whose next-layer top-1 is a successor expert:", affinity)
 
 

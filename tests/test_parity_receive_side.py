@@ -148,24 +148,26 @@ def test_segments_entry_point_edge_cases(lib):
 
 
 def test_mixtral_shape_receiver_sampled(lib):
-    """4 ranks x 1024 tokens of the Mixtral-8x7B shape, EP=4 contiguous map: receiver 0's segment FFN on
-    sampled rows (first, last and random rows of every segment) against the oracle."""
+    """4 ranks x 1024 tokens of the Mixtral-8x7B shape, EP=4 contiguous map: receiver 0's buffer and segment table
+    bit for bit against the oracle's exchange, and its segment FFN on sampled rows (first, last and random rows of
+    every segment) against the oracle run on the oracle's own receive buffer."""
     G, T_rank, d, f, E, k = 4, 1024, 4096, 14336, 8, 2
     pl = np.repeat(np.arange(G), E // G).astype(np.int32)
     grp, weights, xs, lgs = make_group(77, G, T_rank, d, f, E, k, "bf16", pl)
     grp.forward([to_device(x) for x in xs], [torch.from_numpy(l).cuda() for l in lgs])
     torch.cuda.synchronize()
     got = grp.received[0]
+    dsps = [O.dispatch(xs[r], O.topk_gate(lgs[r], k)[0], pl, G) for r in range(G)]
+    ex = O.exchange_to(dsps, pl, 0)
+    np.testing.assert_array_equal(to_host(got["recv_buf"]).reshape(ex["recv_buf"].shape), ex["recv_buf"])
+    for n in ("seg_expert", "seg_counts", "seg_start"):
+        np.testing.assert_array_equal(got[n].cpu().numpy(), ex[n])
     rng = np.random.default_rng(0)
     pos = []
-    seg_expert, seg_counts, seg_start = (got[n].cpu().numpy() for n in ("seg_expert", "seg_counts", "seg_start"))
-    for c, s in zip(seg_counts, seg_start):
+    for c, s in zip(ex["seg_counts"], ex["seg_start"]):
         if c:
             pos += [int(s), int(s + c - 1)] + (s + rng.integers(0, c, 6)).tolist()
     pos = np.unique(np.array(pos, dtype=np.int64))
-    recv = to_host(got["recv_buf"])
-    ref = O.expert_ffn_segments(recv, *weights, seg_expert, seg_counts, seg_start, positions=pos)
+    ref = O.expert_ffn_segments(ex["recv_buf"], *weights, ex["seg_expert"], ex["seg_counts"], ex["seg_start"], positions=pos)
     out = as_f64(to_host(got["out"][torch.from_numpy(pos).cuda()]))
     assert rel_err(out, ref[pos]) <= TOL_BF16
-    assert fro_err(out, ref[pos]) <= TOL_BF16
-    assert len(got["seg_expert"]) == G * (E // G) and got["seg_counts"].sum() == recv.shape[0]
