@@ -16,41 +16,53 @@ namespace moe {
 constexpr int kLdsBins = 12288;          // 48 KB of int32 per workgroup
 constexpr int kTokPerThread = 4;
 
-template <bool USE_LDS>
-__global__ __launch_bounds__(256) void transition_kernel(const int32_t* __restrict__ idx_l, const int32_t* __restrict__ idx_l1,
+template <bool USE_LDS, int kTransThreads>
+__global__ __launch_bounds__(kTransThreads) void transition_kernel(const int32_t* __restrict__ idx_l, const int32_t* __restrict__ idx_l1,
                                                          int T, int k_l, int k_l1, int use_l, int use_l1, int E_l, int E_l1,
                                                          int copies, int pairs_of_two, unsigned long long* __restrict__ R) {
     extern __shared__ int hist[];
     const int bins = E_l * E_l1;
     const int my_copy = threadIdx.x & (copies - 1);
     if (USE_LDS) {
-        for (int b = threadIdx.x; b < bins * copies; b += 256) hist[b] = 0;
+        for (int b = threadIdx.x; b < bins * copies; b += kTransThreads) hist[b] = 0;
         __syncthreads();
     }
-    const long long stride = (long long)gridDim.x * 256;
+    const long long stride = (long long)gridDim.x * kTransThreads;
     auto count = [&](int e1, int e2) {
         if ((unsigned)e1 >= (unsigned)E_l || (unsigned)e2 >= (unsigned)E_l1) return;
         if (USE_LDS) atomicAdd(&hist[(e1 * E_l1 + e2) * copies + my_copy], 1);
         else atomicAdd(&R[e1 * E_l1 + e2], 1ull);
     };
-    long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    long long t = (long long)blockIdx.x * kTransThreads + threadIdx.x;
     if (pairs_of_two) {
-        // top-2 in both layers (the usual case) and 8-byte aligned arrays: 8-byte loads, four tokens per thread in flight at a time
+        // top-2 in both layers (the usual case) and 8-byte aligned arrays: 8-byte loads, eight tokens per thread in flight at a time
         const int2* a2 = reinterpret_cast<const int2*>(idx_l);
         const int2* b2 = reinterpret_cast<const int2*>(idx_l1);
-        for (; t + 3 * stride < T; t += 4 * stride) {
+        auto count_pairs = [&](int2 a, int2 b) {
+            count(a.x, b.x);
+            if (use_l1 > 1) count(a.x, b.y);
+            if (use_l > 1) {
+                count(a.y, b.x);
+                if (use_l1 > 1) count(a.y, b.y);
+            }
+        };
+        for (; t + 7 * stride < T; t += 8 * stride) {
+            int2 a[8], b[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { a[u] = a2[t + u * stride]; b[u] = b2[t + u * stride]; }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) count_pairs(a[u], b[u]);
+        }
+        for (; t < T; t += 4 * stride) {                   // the tail: slots past the batch hold -1, which count() ignores
             int2 a[4], b[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { a[u] = a2[t + u * stride]; b[u] = b2[t + u * stride]; }
-#pragma unroll
             for (int u = 0; u < 4; ++u) {
-                count(a[u].x, b[u].x);
-                if (use_l1 > 1) count(a[u].x, b[u].y);
-                if (use_l > 1) {
-                    count(a[u].y, b[u].x);
-                    if (use_l1 > 1) count(a[u].y, b[u].y);
-                }
+                const bool in = t + u * stride < T;
+                a[u] = in ? a2[t + u * stride] : make_int2(-1, -1);
+                b[u] = in ? b2[t + u * stride] : make_int2(-1, -1);
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) count_pairs(a[u], b[u]);
         }
     }
     if (use_l <= 8 && use_l1 <= 8) {
@@ -80,7 +92,7 @@ __global__ __launch_bounds__(256) void transition_kernel(const int32_t* __restri
     }
     if (USE_LDS) {
         __syncthreads();
-        for (int b = threadIdx.x; b < bins; b += 256) {
+        for (int b = threadIdx.x; b < bins; b += kTransThreads) {
             int c = 0;
             for (int i = 0; i < copies; ++i) c += hist[b * copies + ((i + threadIdx.x) & (copies - 1))];
             if (c) atomicAdd(&R[b], (unsigned long long)c);
@@ -96,17 +108,29 @@ int launch_transition(const int32_t* idx_l, const int32_t* idx_l1, int T, int k_
     // tokens per thread: four for top-2 x top-2, one when a token has 16 pairs or more
     const int pairs = use_l * use_l1;
     const int tpt = pairs >= 16 ? 1 : (pairs >= 8 ? 2 : kTokPerThread);
-    long long want = ((long long)T + 256 * tpt - 1) / (256 * tpt);
-    const unsigned grid = (unsigned)(want < 1 ? 1 : (want > 512 ? 512 : want));
+    // Every workgroup ends with one global atomic per non-zero bin, all workgroups on the same few lines: at most 512
+    // workgroups of 256 threads; batches that would need more run 256 workgroups of 1024 threads instead (as many
+    // threads, half the atomics: 24.7 -> 18.5 us at 4 M tokens, top-2 x top-2), which a small batch cannot afford
+    // (one large workgroup starts more slowly than four small ones)
+    const long long want256 = ((long long)T + 256 * tpt - 1) / (256 * tpt);
+    const bool large = want256 > 512;
+    const long long want = large ? ((long long)T + 1024 * tpt - 1) / (1024 * tpt) : want256;
+    const long long cap = large ? 256 : 512;
+    const unsigned grid = (unsigned)(want < 1 ? 1 : (want > cap ? cap : want));
     int copies = 1;
     while (copies < 32 && bins * copies * 2 <= kLdsBins) copies *= 2;
     LaunchTimer timer(MOE_K_TRANSITION, s);
-    if (bins <= kLdsBins)
-        hipLaunchKernelGGL(transition_kernel<true>, dim3(grid), dim3(256), bins * copies * sizeof(int), s, idx_l, idx_l1, T, k_l, k_l1,
-                           use_l, use_l1, E_l, E_l1, copies, pairs_of_two, (unsigned long long*)R);
-    else
-        hipLaunchKernelGGL(transition_kernel<false>, dim3(grid), dim3(256), 0, s, idx_l, idx_l1, T, k_l, k_l1, use_l, use_l1, E_l, E_l1, 1,
-                           pairs_of_two, (unsigned long long*)R);
+#define MOE_LAUNCH_TRANSITION(LDS, THREADS, SMEM, COPIES)                                                                          \
+    hipLaunchKernelGGL((transition_kernel<LDS, THREADS>), dim3(grid), dim3(THREADS), SMEM, s, idx_l, idx_l1, T, k_l, k_l1, use_l, use_l1, \
+                       E_l, E_l1, COPIES, pairs_of_two, (unsigned long long*)R)
+    if (bins <= kLdsBins) {
+        if (large) MOE_LAUNCH_TRANSITION(true, 1024, bins * copies * sizeof(int), copies);
+        else MOE_LAUNCH_TRANSITION(true, 256, bins * copies * sizeof(int), copies);
+    } else {
+        if (large) MOE_LAUNCH_TRANSITION(false, 1024, 0, 1);
+        else MOE_LAUNCH_TRANSITION(false, 256, 0, 1);
+    }
+#undef MOE_LAUNCH_TRANSITION
     return check_launch("moe_transition_counts launch");
 }
 

@@ -71,6 +71,20 @@ def test_top1_pairs_match_oracle(lib, T, E1, E2, k1, k2):
     np.testing.assert_array_equal(run(lib, a, b, E1, E2), O.transition_counts(a, b, E1, E2))
 
 
+def test_many_pairs_per_token_at_a_size_that_takes_the_large_workgroups(lib):
+    """top-6 x top-6 over 64 experts, 150000 tokens: more than 512 workgroups of 256 threads would be needed, so the
+    launch switches to 1024-thread workgroups.  Marginal identities, the total, and sampled bins counted one by one."""
+    T, E, k = 150000, 64, 6
+    a = synth.random_topk_idx(23, T, E, k)
+    b = synth.random_topk_idx(24, T, E, k)
+    R = run(lib, a, b, E, E)
+    np.testing.assert_array_equal(R.sum(axis=1), k * np.bincount(a.reshape(-1), minlength=E))
+    np.testing.assert_array_equal(R.sum(axis=0), k * np.bincount(b.reshape(-1), minlength=E))
+    assert R.sum() == T * k * k
+    for e1, e2 in [(0, 0), (13, 50), (63, 1), (31, 32)]:
+        assert R[e1, e2] == int(((a == e1).any(axis=1) & (b == e2).any(axis=1)).sum())
+
+
 def test_top1_pairs_large_batch_marginals(lib):
     T, E, k = 1 << 20, 8, 2
     a = synth.random_topk_idx(13, T, E, k)
