@@ -242,11 +242,15 @@ def main():
     up_bit = 1 << B.KERNEL_NAMES.index("ffn_up")
     B.moe_timing_begin(up_bit, args.steps + 4)
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # step boundaries, for min / max
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
     ms_sum, launches = B.moe_timing_end()
     ms_per_step = elapsed / args.steps * 1e3
 
@@ -276,6 +280,7 @@ def main():
     out = {
         "metric": "MoE-layer tokens/s on 1 MI355X (Mixtral-8x7B shape)", "value": round(cfg.T / (ms_per_step * 1e-3), 1),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_min": round(min(per_step), 4), "ms_per_step_max": round(max(per_step), 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} f={cfg.f} E={cfg.E} top-{cfg.k}, {cfg.dtype}, "
                                f"G={cfg.G} local_gpu={cfg.local_gpu}, Zipf({cfg.zipf_s}) router bias",
