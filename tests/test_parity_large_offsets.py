@@ -3,10 +3,12 @@
 The configurations' own buffers stay below 2^31 bytes, so an element or byte
 offset kept in 32 bits anywhere in the row copy, the combine or the grouped
 GEMM would pass every other test.  Here the send buffer of moe_dispatch is
-4.9 GB (2.46e9 bf16 elements) and the intermediate H of the expert FFN 4.6 GB
-(2.29e9 elements); the rows checked include the last ones, which lie at the
-highest offsets.  Integer outputs and row copies are compared in full, float
-outputs on sampled rows that the oracle computes one by one.
+4.9 GB (2.46e9 bf16 elements), the intermediate H of the expert FFN 4.6 GB
+(2.29e9 elements), the gate's logits and the transition counts' index array
+sit at their documented limits, and the router reads 4.9 GB of activations;
+the rows checked include the last ones, which lie at the highest offsets.
+Integer outputs and row copies are compared in full where the oracle can
+afford it, float outputs on sampled rows that the oracle computes one by one.
 """
 import numpy as np
 import pytest
@@ -101,3 +103,74 @@ def test_expert_ffn_with_an_intermediate_past_2_to_31_elements(lib):
     err = rel_err(got, want)
     print(f"\nffn_out on {len(rows)} sampled rows of {N}: rel_err {err:.3e}")
     assert err <= TOL_BF16
+
+
+def test_gate_at_the_size_limit_of_its_logits(lib):
+    """T * E just under 2^31 (the call's documented limit): the last tokens' logits lie 8.5 GB into the array."""
+    T, E, k = 8_300_000, 256, 8
+    assert T * E < 2 ** 31 and T * E * 4 > 2 ** 32
+    lg = synth.normal(73, 1, (T, E), 2.0, "f32")
+    dl = torch.from_numpy(lg).cuda()
+    idx = torch.full((T, k), -7, dtype=torch.int32, device="cuda")
+    w = torch.full((T, k), -1.0, dtype=torch.float32, device="cuda")
+    lib.moe_topk_gate(dl, T, E, k, idx, w)
+    torch.cuda.synchronize()
+    tokens = ends_and_random(np.random.default_rng(73), T, 256, 4000)
+    sel = torch.from_numpy(tokens).cuda()
+    gi, gw = idx[sel].cpu().numpy(), w[sel].cpu().numpy()
+    oi, ow = O.topk_gate(lg[tokens], k)
+    np.testing.assert_array_equal(gi, oi)
+    assert float(np.max(np.abs(gw.astype(np.float64) - ow) / np.maximum(ow, 1e-30))) <= 1e-4
+    # every token got its k distinct experts: nothing left at the fill value anywhere
+    assert int((idx < 0).sum()) == 0 and int((w < 0).sum()) == 0
+
+
+def test_transition_counts_at_the_size_limit_of_an_index_array(lib):
+    """T * k just under 2^31 entries (the documented limit) in layer l's array: 8.6 GB of indices.  Layer l lists all
+    16 experts per token (a rotation of 0..15 by a seeded offset: cheap to make at this size), layer l+1 one expert,
+    so every row of R is the histogram of layer l+1's choices and the top-1 pairs are (offset, choice)."""
+    T, E, k = 134_000_000, 16, 16
+    assert T * k < 2 ** 31 and T * k * 4 > 2 ** 32
+    rng = np.random.default_rng(74)
+    ra = rng.integers(0, E, size=T, dtype=np.int32)
+    rb = rng.integers(0, E, size=T, dtype=np.int32)
+    base = torch.arange(E, dtype=torch.int32, device="cuda")
+    a = ((torch.from_numpy(ra).cuda()[:, None] + base[None, :]) % E).contiguous()
+    b = torch.from_numpy(rb).cuda().reshape(T, 1)
+    R = torch.zeros((E, E), dtype=torch.int64, device="cuda")
+    lib.moe_transition_counts(a, b, T, k, 1, E, E, R)
+    Rp = torch.zeros((E, E), dtype=torch.int64, device="cuda")
+    lib.moe_transition_counts_pairs(a, b, T, k, 1, E, E, lib.MOE_PAIRS_TOP1, Rp)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(R.cpu().numpy(), np.tile(np.bincount(rb, minlength=E), (E, 1)))
+    want = np.zeros((E, E), dtype=np.int64)
+    np.add.at(want, (ra, rb), 1)
+    np.testing.assert_array_equal(Rp.cpu().numpy(), want)
+
+
+def test_router_gate_with_activations_past_4_GiB(lib):
+    """The fused router reads 4.9 GB of activations; logits and selection of sampled tokens (the last ones included)
+    against the fp64 router, with the margin rule for near ties that the router tests use."""
+    T, d, E, k = 600_000, 4096, 8, 2
+    assert T * d > 2 ** 31
+    x = synth.normal(75, 0, (T, d), 1.0, "bf16")
+    w_g = synth.normal(75, 1, (d, E), 1.0 / np.sqrt(d), "bf16")
+    bias = np.random.default_rng(75).standard_normal(E).astype(np.float32)
+    packed = torch.empty(lib.moe_router_packed_bytes(d, E, lib.MOE_BF16), dtype=torch.uint8, device="cuda")
+    lib.moe_pack_router(to_device(w_g), d, E, lib.MOE_BF16, packed)
+    logits = torch.full((T, E), 7.0, dtype=torch.float32, device="cuda")
+    idx = torch.full((T, k), -1, dtype=torch.int32, device="cuda")
+    w = torch.full((T, k), -1.0, dtype=torch.float32, device="cuda")
+    lib.moe_router_gate(to_device(x), lib.MOE_BF16, packed, torch.from_numpy(bias).cuda(), T, d, E, k, logits, idx, w)
+    torch.cuda.synchronize()
+    assert int((idx < 0).sum()) == 0
+    tokens = ends_and_random(np.random.default_rng(75), T, 64, 2000)
+    sel = torch.from_numpy(tokens).cuda()
+    lg, gi = logits[sel].cpu().numpy(), idx[sel].cpu().numpy()
+    lg_ref, idx_ref, _ = O.router_gate(x[tokens], w_g, bias, k)
+    scale = np.sqrt(np.mean(lg_ref ** 2, axis=1, keepdims=True)) + 1e-30
+    assert np.max(np.abs(lg - lg_ref) / np.maximum(np.abs(lg_ref), scale)) <= 1e-5
+    srt = -np.sort(-lg_ref, axis=1)
+    clear = np.all(srt[:, :k] - srt[:, 1:k + 1] > 2e-5 * scale, axis=1)
+    assert clear.mean() > 0.9
+    np.testing.assert_array_equal(gi[clear], idx_ref[clear])
