@@ -264,10 +264,6 @@ def main():
     roofline = {"bound": "mfma", "kernel": "ffn_up (A.[W1|W3] + SwiGLU)", "achieved": round(achieved, 2), "peak": peak,
                 "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
                 "ms": round(up_ms, 4), "flops_per_launch": up_flops}
-    traffic = measured_traffic(cfg.name)
-    if traffic is not None:
-        roofline["traffic"] = traffic["bytes"]
-        roofline["traffic_source"] = f"profiles/ffn_up_l2_traffic.txt (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, measured on commit {traffic['commit']})"
     if cfg.dtype == "bf16" and cfg.T * cfg.k <= B.FFN_STREAMING_MAX_ROWS:
         # decode-sized batch: the up projection streams every touched expert's W1 and W3 once and is bound by HBM
         touched = int((counts > 0).sum() if cfg.local_gpu < 0 else (counts[pl == cfg.local_gpu] > 0).sum())
@@ -276,6 +272,11 @@ def main():
         roofline = {"bound": "hbm", "kernel": "ffn_up (weight streaming, decode-sized batch)", "achieved": round(gbs, 1),
                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None,
                     "ms": round(up_ms, 4), "bytes_per_launch": up_bytes}
+
+    traffic = measured_traffic(cfg.name)
+    if traffic is not None:
+        roofline["traffic"] = traffic["bytes"]
+        roofline["traffic_source"] = f"profiles/ffn_up_l2_traffic.txt (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, measured on commit {traffic['commit']})"
 
     out = {
         "metric": "MoE-layer tokens/s on 1 MI355X (Mixtral-8x7B shape)", "value": round(cfg.T / (ms_per_step * 1e-3), 1),
