@@ -66,7 +66,7 @@
 // Epilogue.  Accumulators are converted to bf16 (round to nearest even),
 // transposed through a per-wavefront LDS staging tile and written with
 // 16-byte stores that cover whole 128-byte lines.
-#include "ffn_plan.h"
+#include "ffn_tiles.h"
 
 namespace moe {
 
@@ -97,10 +97,6 @@ template <int FM> struct Tile {
     static constexpr size_t kPartialFloats = (size_t)BM * BN;
 };
 constexpr int kPanelCols = 16;
-constexpr int kXcds = 8;
-constexpr int kMaxSplit = 8;
-constexpr int kMinSplitKT = 8;                  // a k part is at least this many k tiles
-constexpr int kMinSplitGain = 16;               // k tiles of time a split tail must save to be worth its fix-up
 constexpr size_t kMaxPartialFloats = (size_t)384 * BN;          // one fp32 partial tile of the largest tile
 
 static inline size_t npad13(int f) { return round_up((size_t)2 * f, BN); }
@@ -111,7 +107,6 @@ size_t packed_bytes_bf16(int E, int d, int f) {
 }
 
 // fp32 partial tiles for the split tail of the down projection: two slots per compute unit
-constexpr int kMaxCusPerXcd = 48;
 size_t ffn_bf16_scratch_bytes() { return (size_t)kXcds * 2 * kMaxCusPerXcd * kMaxPartialFloats * sizeof(float); }
 
 // One thread per 16-byte unit of the packed buffer.  Unit index within one matrix of one expert:
@@ -162,106 +157,6 @@ int launch_pack_bf16(const void* w1, const void* w3, const void* w2, int E, int 
     hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)grid), dim3(256), 0, s, (const uint16_t*)w1, (const uint16_t*)w3,
                        (const uint16_t*)w2, d, f, units13, units2, total, (uint4*)packed);
     return check_launch("moe_pack_weights launch");
-}
-
-// ---------------------------------------------------------------------------
-// which piece of work does this workgroup (or fix-up block) own?
-// ---------------------------------------------------------------------------
-struct WorkItem {
-    int expert, row0, rows, nt;
-    int kt0, kt1;        // k tile range
-    int partial;         // slot of the fp32 partial tile, or -1 for a whole tile
-    int parts;           // split factor of this tile (fix-up only)
-};
-
-struct XcdShare {
-    int q, rem;          // column tiles owned outright by every XCD; left-over column tiles (NT % 8)
-    long long main;      // tiles of the owned columns: row tiles x q
-    long long rem_begin; // this XCD's first tile in the list of left-over-column tiles
-    int full;            // tiles run whole
-    int tail;            // tiles run in `split` k parts each
-    int split;
-};
-
-// The tiles of XCD x.  Every XCD owns NT / 8 column tiles of every expert outright, so each weight
-// panel is fetched through one L2 only and all XCDs get the same mix of large and small experts; the
-// tiles of the NT % 8 left-over column tiles are dealt to the XCDs in equal contiguous ranges.
-__device__ __forceinline__ XcdShare xcd_share(int MT, int NT, int x, int KT, int cus_per_xcd, bool allow_split) {
-    XcdShare s;
-    s.q = NT / kXcds;
-    s.rem = NT - s.q * kXcds;
-    s.main = (long long)MT * s.q;
-    const long long rem_total = (long long)MT * s.rem;
-    const long long chunk = (rem_total + kXcds - 1) / kXcds;
-    s.rem_begin = (long long)x * chunk;
-    long long rcnt = rem_total - s.rem_begin;
-    rcnt = rcnt < 0 ? 0 : (rcnt > chunk ? chunk : rcnt);
-    const long long cnt = s.main + rcnt;
-    s.full = (int)cnt;
-    s.tail = 0;
-    s.split = 1;
-    if (allow_split) {
-        // r tiles in the last round: cut each into sp k parts so that the r * sp parts (at most two per
-        // compute unit: that many partial tiles exist) fill the compute units in as few, short rounds as
-        // possible; taken when the tail then lasts at most three quarters of a whole round
-        const int r = (int)(cnt % cus_per_xcd);
-        if (r > 0) {
-            int best = 1, best_num = 1, best_den = 1;           // tail time = best_num / best_den rounds
-            for (int sp = 2; sp <= kMaxSplit; ++sp) {
-                if (r * sp > 2 * cus_per_xcd || KT / sp < kMinSplitKT) break;
-                const int rounds = (r * sp + cus_per_xcd - 1) / cus_per_xcd;
-                if (rounds * best_den < best_num * sp) { best = sp; best_num = rounds; best_den = sp; }
-            }
-            // ... and saves at least kMinSplitGain k tiles of time: the partial tiles and the fix-up launch cost
-            // about that much, so short reductions (the many-expert layer: 22 k tiles) run their tail whole
-            if (best > 1 && 4 * best_num <= 3 * best_den && (best_den - best_num) * KT >= kMinSplitGain * best_den) {
-                s.full = (int)cnt - r;
-                s.tail = r;
-                s.split = best;
-            }
-        }
-    }
-    return s;
-}
-
-// Tile order inside one expert: row tiles are taken in chunks of `row_chunk`, and within a chunk the
-// column tile advances before the chunk does, so the ~32 tiles that run together on an XCD form a
-// row_chunk x (32 / row_chunk) block that streams row_chunk activation panels and 32 / row_chunk
-// weight panels through that XCD's L2 (a large expert would otherwise run as a 32 x 1 strip that
-// re-reads its activations once per column tile).  Every chunk re-reads the expert's weights, which
-// come from DRAM, while re-read activations come from the Infinity Cache as long as they fit there:
-// chunks of 8 row tiles then, of 4 (the split that moves the fewest bytes) for larger batches.
-constexpr size_t kActivationsFitCache = (size_t)128 << 20;
-static inline int row_chunk_for(size_t activation_bytes) { return activation_bytes <= kActivationsFitCache ? 8 : 4; }
-
-__device__ __forceinline__ void locate_tile(const int32_t* __restrict__ plan, const int32_t* __restrict__ prefix, int NT,
-                                            long long tile, int BM, int row_chunk, WorkItem& w) {
-    const int n_exp = plan[0];
-    int i = 0;
-    while (i + 1 < n_exp && (long long)prefix[i + 1] * NT <= tile) ++i;
-    const int mt_e = prefix[i + 1] - prefix[i];
-    const int rem = (int)(tile - (long long)prefix[i] * NT);
-    const int per_chunk = row_chunk * NT;
-    const int q = rem / per_chunk;                       // chunk of row tiles
-    const int in_chunk = rem - q * per_chunk;
-    const int rows_here = min(row_chunk, mt_e - q * row_chunk);
-    w.nt = in_chunk / rows_here;
-    const int mt = q * row_chunk + (in_chunk - w.nt * rows_here);
-    w.expert = plan[kPlanExpert + i];
-    w.row0 = plan[kPlanStart + i] + mt * BM;
-    w.rows = min(BM, plan[kPlanCount + i] - mt * BM);
-}
-
-// tile `idx` of XCD x's list: first the tiles of its own column tiles, then its share of the left-over ones
-__device__ __forceinline__ void locate_xcd_tile(const int32_t* __restrict__ plan, const int32_t* __restrict__ prefix,
-                                                const XcdShare& sh, int x, int idx, int BM, int row_chunk, WorkItem& w) {
-    if (idx < sh.main) {
-        locate_tile(plan, prefix, sh.q, idx, BM, row_chunk, w);
-        w.nt += x * sh.q;
-    } else {
-        locate_tile(plan, prefix, sh.rem, sh.rem_begin + (idx - sh.main), BM, row_chunk, w);
-        w.nt += kXcds * sh.q;
-    }
 }
 
 // ---------------------------------------------------------------------------
@@ -591,21 +486,8 @@ __device__ __forceinline__ void ffn_tile(uint16_t* smem, const uint16_t* __restr
     constexpr int BM = Tile<FM>::BM;
     const int32_t* prefix = plan + (FM == 3 ? kPlanTiles0 : kPlanTiles1);
     const int NT = npad / BN, KT = K / BK;
-    const int x = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
-    const XcdShare sh = xcd_share(prefix[plan[0]], NT, x, KT, cus_per_xcd, SPLIT);
-    if (slot >= sh.full + sh.tail * sh.split) return;
     WorkItem w;
-    if (slot < sh.full) {
-        locate_xcd_tile(plan, prefix, sh, x, slot, BM, row_chunk, w);
-        w.kt0 = 0; w.kt1 = KT; w.partial = -1;
-    } else {
-        const int j = slot - sh.full;
-        const int part = j % sh.split;
-        locate_xcd_tile(plan, prefix, sh, x, sh.full + j / sh.split, BM, row_chunk, w);
-        w.kt0 = (int)((long long)part * KT / sh.split);
-        w.kt1 = (int)((long long)(part + 1) * KT / sh.split);
-        w.partial = x * 2 * cus_per_xcd + j;
-    }
+    if (!workgroup_item(plan, prefix, NT, KT, BM, blockIdx.x, cus_per_xcd, row_chunk, SPLIT, w)) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -673,10 +555,9 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
     const int32_t* prefix = plan + (tall ? kPlanTiles0 : kPlanTiles1);
     const int NT = npad / BN, KT = K / BK;
     const int x = blockIdx.x % kXcds, q = (blockIdx.x / kXcds) / fm, j = (blockIdx.x / kXcds) % fm;
-    const XcdShare sh = xcd_share(prefix[plan[0]], NT, x, KT, cus_per_xcd, true);
-    if (q >= sh.tail) return;
     WorkItem w;
-    locate_xcd_tile(plan, prefix, sh, x, sh.full + q, BM, row_chunk, w);
+    int first_partial, parts;
+    if (!fixup_item(plan, prefix, NT, KT, BM, x, q, cus_per_xcd, row_chunk, w, first_partial, parts)) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if (j >= active_blocks(w.rows, wave / WN, fm)) return;
@@ -687,8 +568,8 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
         for (int b = 0; b < FN; ++b)
 #pragma unroll
             for (int v = 0; v < 4; ++v) blk[h][b][v] = 0.f;
-    for (int part = 0; part < sh.split; ++part) {
-        const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(x * 2 * cus_per_xcd + q * sh.split + part) * partial_floats) + tid;
+    for (int part = 0; part < parts; ++part) {
+        const f32x4* src = reinterpret_cast<const f32x4*>(partials + (size_t)(first_partial + part) * partial_floats) + tid;
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -722,12 +603,7 @@ struct FfnCall {
     int cpx, chunk_up, chunk_down;
     size_t s13, stride;
     float* partials;
-    long long grid_for(size_t npad, int bm, bool split) const {
-        const long long mt_max = (N + bm - 1) / bm + (E < N ? E : N);     // sum of ceil(n_e / bm) never exceeds this
-        const long long nt = (long long)(npad / BN);
-        const long long per_xcd = mt_max * (nt / kXcds) + (mt_max * (nt % kXcds) + kXcds - 1) / kXcds;
-        return (long long)kXcds * (per_xcd + (split ? 2 * cpx : 0));
-    }
+    long long grid_for(size_t npad, int bm, bool split) const { return ffn_grid(N, E, (long long)(npad / BN), bm, split, cpx); }
 };
 
 template <bool UP>
