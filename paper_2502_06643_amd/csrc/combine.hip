@@ -107,8 +107,7 @@ __global__ __launch_bounds__(256) void combine_token_kernel(const uint4* __restr
     };
     if (k <= 8 && local_gpu < 0) {
         // every expert resident: the token's positions and weights are all fetched before any is used
-        // (independent wave-uniform loads instead of a dependent chain per route).  With a resident subset
-        // the chain below is faster: most routes are skipped after two short loads.
+        // (independent wave-uniform loads instead of a dependent chain per route)
         int p[8];
         float w[8];
 #pragma unroll
@@ -120,20 +119,24 @@ __global__ __launch_bounds__(256) void combine_token_kernel(const uint4* __restr
         for (int j = 0; j < 8; ++j)
             if ((unsigned)p[j] < (unsigned)N) add_row(p[j], w[j]);
     } else if (k <= 8) {
-        // a resident subset of the experts: the token's k expert ids, then their k owners, are fetched as
-        // two rounds of independent wave-uniform loads; only the routes that turn out to be local (one in
-        // G on average) go on to their position, weight and row
-        int ex[8], owner[8];
+        // a resident subset of the experts: the token's k expert ids, positions and weights, then the k
+        // owners, are fetched as two rounds of independent wave-uniform loads; only the routes that turn out
+        // to be local (one in G on average) go on to their row
+        int ex[8], owner[8], p[8];
+        float w[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) ex[j] = (j < k) ? topk_idx[t * k + j] : -1;
+        for (int j = 0; j < 8; ++j) {
+            ex[j] = (j < k) ? topk_idx[t * k + j] : -1;
+            p[j] = (j < k) ? inv_perm[t * k + j] : -1;
+            w[j] = (j < k) ? topk_w[t * k + j] : 0.f;
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) owner[j] = ((unsigned)ex[j] < (unsigned)E) ? placement[ex[j]] : -1;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             if (j >= k || owner[j] != local_gpu) continue;
-            const int p = inv_perm[t * k + j];
-            if ((unsigned)p >= (unsigned)N) continue;
-            add_row(p, topk_w[t * k + j]);
+            if ((unsigned)p[j] >= (unsigned)N) continue;
+            add_row(p[j], w[j]);
         }
     } else {
         for (int j = 0; j < k; ++j) {
