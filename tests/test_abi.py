@@ -86,6 +86,19 @@ def test_bad_scalars_are_rejected_without_touching_the_gpu():
     assert L.moe_receive_segments(one, one, 8, 4, 4, 8, one, one, one, None, None, None) == -1                              # dest outside [0,G)
     assert L.moe_receive_segments(one, one, 8, 4, 0, 257, one, one, one, None, None, None) == -1                            # more segments than the segment FFN takes
     assert L.moe_receive_segments(one, one, 8, 4, 0, 8, one, None, one, None, None, None) == -1                             # NULL table
+    # the fused router and the placement evaluators
+    assert L.moe_router_gate(one, 1, one, None, -1, 128, 8, 2, None, one, one, None) == -1                                  # T < 0
+    assert L.moe_router_gate(one, 1, one, None, 4, 100, 8, 2, None, one, one, None) == -2                                   # bf16 needs d % 64 == 0
+    assert L.moe_router_gate(one, 1, one, None, 4, 128, 8, 9, None, one, one, None) == -1                                   # k > E
+    assert L.moe_router_gate(one, 1, None, None, 4, 128, 8, 2, None, one, one, None) == -1                                  # no packed router
+    assert L.moe_router_packed_bytes(100, 8, 1) == 0 and L.moe_router_packed_bytes(128, 8, 1) >= 128 * 8 * 2
+    assert L.moe_pack_router(one, 128, 8, 1, one, 16, None) == -3                                                           # packed buffer too small
+    assert L.moe_accumulate_counts(one, 0, one, None) == -1
+    assert L.moe_accumulate_counts(None, 8, one, None) == -1
+    assert L.moe_placement_loads(one, one, 8, 0, one, None, None) == -1                                                     # G = 0
+    assert L.moe_placement_loads(one, None, 8, 4, one, None, None) == -1
+    assert L.moe_placement_traffic(one, one, one, 8, 300, 4, one, None, None, None) == -1                                   # E_l1 too large
+    assert L.moe_placement_traffic(one, one, one, 8, 8, 4, None, None, None, None) == -1                                    # no output
     assert L.moe_timing_begin(1, 0) == -1
     # empty batches are fine and enqueue nothing
     assert L.moe_topk_gate(None, 0, 8, 2, None, None, None) == 0
