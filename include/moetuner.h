@@ -395,8 +395,10 @@ int moe_placement_traffic(const int64_t* R, const int32_t* placement_l, const in
  * a pair of HIP events on the stream it is launched on.  moe_timing_end
  * waits for the recorded events, then fills (host arrays of MOE_K_COUNT
  * entries) the summed milliseconds and the number of launches per kernel id.
- * At most max_records launches are recorded; later ones run untimed.  Not
- * thread-safe; one timing session at a time.
+ * At most max_records launches are recorded; later ones run untimed.  One
+ * session at a time per process, begun and ended by one thread; launches
+ * from other threads while it is open are recorded too, but no library call
+ * may be in flight on another thread while moe_timing_end runs.
  * ---------------------------------------------------------------------- */
 int moe_timing_begin(unsigned mask, int max_records);
 int moe_timing_end(double* sum_ms /*host [MOE_K_COUNT]*/, int* launches /*host [MOE_K_COUNT]*/);

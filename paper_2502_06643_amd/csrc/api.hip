@@ -3,7 +3,9 @@
 // combine.hip, transition.hip).
 #include "common.h"
 #include <cstdarg>
+#include <atomic>
 #include <cstdio>
+#include <mutex>
 #include <vector>
 
 namespace moe {
@@ -23,30 +25,38 @@ int hip_fail(hipError_t e, const char* what) {
 }
 
 // ---- timing session -----------------------------------------------------------
+// One session per process.  The mask is atomic and the record table is guarded, so launches from several
+// host threads may run while a session is open; begin and end themselves are for one controlling thread.
 struct TimingRecord { int kid; hipEvent_t start, stop; };
-static unsigned g_mask = 0;
+static std::atomic<unsigned> g_mask{0};
+static std::mutex g_timing_mutex;
 static int g_used = 0;
 static std::vector<TimingRecord> g_records;
 
 LaunchTimer::LaunchTimer(int kernel_id, hipStream_t stream) : slot_(-1), stream_(stream) {
-    if (!(g_mask & (1u << kernel_id)) || g_used >= (int)g_records.size()) return;
+    if (!(g_mask.load(std::memory_order_acquire) & (1u << kernel_id))) return;
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    if (!(g_mask.load(std::memory_order_relaxed) & (1u << kernel_id)) || g_used >= (int)g_records.size()) return;
     slot_ = g_used++;
     g_records[slot_].kid = kernel_id;
-    (void)hipEventRecord(g_records[slot_].start, stream_);
+    start_ = g_records[slot_].start;
+    stop_ = g_records[slot_].stop;
+    (void)hipEventRecord(start_, stream_);
 }
 
 LaunchTimer::~LaunchTimer() {
-    if (slot_ >= 0) (void)hipEventRecord(g_records[slot_].stop, stream_);
+    if (slot_ >= 0) (void)hipEventRecord(stop_, stream_);
 }
 
+// caller holds g_timing_mutex
 static void destroy_records() {
+    g_mask.store(0, std::memory_order_release);
     for (auto& r : g_records) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
     }
     g_records.clear();
     g_used = 0;
-    g_mask = 0;
 }
 
 }  // namespace moe
@@ -63,6 +73,7 @@ const char* moe_version(void) { return "moetuner-hip 0.1 (gfx950)"; }
 
 int moe_timing_begin(unsigned mask, int max_records) {
     REQUIRE(max_records > 0 && max_records <= (1 << 20), "moe_timing_begin: max_records=%d out of range", max_records);
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
     destroy_records();
     g_records.resize(max_records);
     for (int i = 0; i < max_records; ++i) {
@@ -74,13 +85,15 @@ int moe_timing_begin(unsigned mask, int max_records) {
             return hip_fail(e, "hipEventCreate");
         }
     }
-    g_mask = mask;
+    g_mask.store(mask, std::memory_order_release);
     return MOE_OK;
 }
 
 int moe_timing_end(double* sum_ms, int* launches) {
     REQUIRE(sum_ms && launches, "moe_timing_end: NULL output");
     for (int i = 0; i < MOE_K_COUNT; ++i) { sum_ms[i] = 0.0; launches[i] = 0; }
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    g_mask.store(0, std::memory_order_release);          // launches from here on are not timed
     int rc = MOE_OK;
     for (int i = 0; i < g_used; ++i) {
         hipError_t e = hipEventSynchronize(g_records[i].stop);

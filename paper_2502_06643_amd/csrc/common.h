@@ -23,6 +23,7 @@ public:
 private:
     int slot_;
     hipStream_t stream_;
+    hipEvent_t start_ = nullptr, stop_ = nullptr;
 };
 
 inline int check_launch(const char* what) {
