@@ -35,11 +35,12 @@
  *    are then unspecified.
  *  - Stream capture: the hot calls record kernels only (no memset, no copy, no
  *    synchronisation), so a caller may capture them into a HIP graph.  The
- *    first bf16 moe_expert_ffn_grouped / _segments call of a process queries
- *    the device and raises its kernels' LDS limits (host-side calls whose
- *    results, including a failure, are kept for the life of the process), and
- *    the first moe_dispatch_noalloc call on a device looks up its scratch
- *    buffer: make one call of each entry point you use before a capture begins.
+ *    first bf16 moe_expert_ffn_grouped / _segments call on each device
+ *    queries the device and raises its kernels' LDS limits (host-side calls;
+ *    the result is kept per device, a failure is reported and tried again by
+ *    the next call), and the first moe_dispatch_noalloc call on a device
+ *    looks up its scratch buffer: make one call of each entry point you use,
+ *    on each device you use, before a capture begins.
  *  - Tokens t in [0,T); experts e in [0,E); a token's j-th choice is route
  *    r = t*k + j (j = 0 is the top-1 expert); N = T*k routes.
  *  - Row-major everywhere.  Activations are MOE_F32 (float) or MOE_BF16

@@ -67,6 +67,7 @@
 // transposed through a per-wavefront LDS staging tile and written with
 // 16-byte stores that cover whole 128-byte lines.
 #include "ffn_tiles.h"
+#include <mutex>
 
 namespace moe {
 
@@ -581,17 +582,6 @@ __global__ __launch_bounds__(kThreads) void ffn_bf16_fixup_kernel(int K, int npa
     epilogue_block<false>(blk[0], blk[1], block_row(j, wave / WN), smem, C, ldc, w, wave, lane);
 }
 
-static int cus_per_xcd() {
-    // initialised once, thread-safe (function-local static)
-    static const int cached = [] {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= kXcds)
-            return cus / kXcds < kMaxCusPerXcd ? cus / kXcds : kMaxCusPerXcd;
-        return 32;
-    }();
-    return cached;
-}
-
 template <typename Kernel>
 static int set_smem(Kernel k, int bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
@@ -609,15 +599,32 @@ struct FfnCall {
 template <bool UP>
 constexpr int launch_smem() { return smem_bytes<UP, 3>() > smem_bytes<UP, 2>() ? smem_bytes<UP, 3>() : smem_bytes<UP, 2>(); }
 
-static int configure() {
-    // the LDS sizes of the three kernels are raised once per process, thread-safe (function-local static)
-    static const int rc = [] {
-        int r;
+// Per-device set-up, done on the first call on each device (not during a stream capture: it calls
+// hipFuncSetAttribute): the LDS sizes of the three kernels are raised and the compute units per XCD are read.
+// A failure is reported and tried again by the next call rather than remembered.
+static int device_setup(int* cus_per_xcd) {
+    constexpr int kMaxDevices = 64;
+    struct Setup { bool done; int cpx; };
+    static std::mutex mutex;
+    static Setup setup[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(MOE_ERR_UNSUPPORTED, "moe_expert_ffn_grouped: device %d outside [0,%d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(mutex);
+    Setup& st = setup[dev];
+    if (!st.done) {
+        int r, cus = 0;
         if ((r = set_smem(&ffn_bf16_kernel<true, false>, launch_smem<true>())) != MOE_OK) return r;
         if ((r = set_smem(&ffn_bf16_kernel<false, true>, launch_smem<false>())) != MOE_OK) return r;
-        return set_smem(&ffn_bf16_fixup_kernel, epilogue_bytes<false>());
-    }();
-    return rc;
+        if ((r = set_smem(&ffn_bf16_fixup_kernel, epilogue_bytes<false>())) != MOE_OK) return r;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return hip_fail(e, "hipDeviceGetAttribute");
+        st.cpx = cus >= kXcds ? (cus / kXcds < kMaxCusPerXcd ? cus / kXcds : kMaxCusPerXcd) : 32;
+        st.done = true;
+    }
+    *cus_per_xcd = st.cpx;
+    return MOE_OK;
 }
 
 // the two projections; bm = the smallest tile height the plan may choose (it sizes the grid)
@@ -661,14 +668,15 @@ int launch_ffn_bf16(const void* a, int N, int d, int f, int E, const void* packe
     // hold kLargeBucketRows rows or more on average.  When every row is in a resident bucket the host
     // knows that average; otherwise only the device does and the plan decides.  Either way the choice
     // reaches the kernels through the plan's header.
+    int cpx = 0;
+    if ((rc = device_setup(&cpx)) != MOE_OK) return rc;
     const bool every_row_resident = local_gpu < 0 && group_expert == nullptr;
     const int choice = every_row_resident ? ((long long)N >= (long long)kLargeBucketRows * E ? 0 : 1) : -1;
-    if ((rc = configure()) != MOE_OK) return rc;
     rc = launch_ffn_plan(counts, starts, placement, local_gpu, group_expert, n_weights, E, N, Tile<3>::BM, Tile<2>::BM, choice, plan, s);
     if (rc != MOE_OK) return rc;
     FfnCall c;
     c.a = a; c.N = N; c.d = d; c.f = f; c.E = E; c.packed = packed; c.out = out; c.plan = plan; c.H = H; c.s = s;
-    c.cpx = cus_per_xcd();
+    c.cpx = cpx;
     c.chunk_up = row_chunk_for((size_t)N * d * 2);
     c.chunk_down = row_chunk_for((size_t)N * f * 2);
     c.s13 = npad13(f) * d;
