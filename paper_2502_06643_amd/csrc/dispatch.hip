@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(int32_t* __
     if (e < E)
         for (int b = b0; b < b1; ++b) sum += block_counts[(size_t)b * E + e];
     slice_tot[threadIdx.x] = sum;
-    if (threadIdx.x < E) pl[threadIdx.x] = placement[threadIdx.x];
+    if ((int)threadIdx.x < E) pl[threadIdx.x] = placement[threadIdx.x];
     __syncthreads();
     if (e < E) {
         int run = 0;
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(int32_t* __
         }
     }
     __syncthreads();
-    if (threadIdx.x < E) {
+    if ((int)threadIdx.x < E) {
         const int me = threadIdx.x;
         int start = 0;
         const int ge = pl[me];
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kFusedThreads) void dispatch_index_kernel(const int
     __shared__ int tot[MOE_MAX_EXPERTS];
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     for (int i = threadIdx.x; i < kFusedWaves * MOE_MAX_EXPERTS; i += kFusedThreads) (&woff[0][0])[i] = 0;
-    if (threadIdx.x < E) pl[threadIdx.x] = placement[threadIdx.x];
+    if ((int)threadIdx.x < E) pl[threadIdx.x] = placement[threadIdx.x];
     __syncthreads();
 
     const int wbase = wave * ITEMS * 64;                                // ITEMS 64-route steps per wavefront
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(kFusedThreads) void dispatch_index_kernel(const int
     for (int i = 0; i < ITEMS; ++i)
         if ((unsigned)exs[i] < (unsigned)E) atomicAdd(&woff[wave][exs[i]], 1);   // LDS atomics: counts need no order
     __syncthreads();
-    if (threadIdx.x < E) {
+    if ((int)threadIdx.x < E) {
         int t = 0;
 #pragma unroll
         for (int w = 0; w < kFusedWaves; ++w) t += woff[w][threadIdx.x];
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(kFusedThreads) void dispatch_index_kernel(const int
         expert_counts[threadIdx.x] = t;
     }
     __syncthreads();
-    if (threadIdx.x < E) {
+    if ((int)threadIdx.x < E) {
         const int me = threadIdx.x, ge = pl[me];
         int start = 0;
 #pragma unroll 8

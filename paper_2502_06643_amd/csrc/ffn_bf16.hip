@@ -309,7 +309,7 @@ template <int FM>
 __device__ __forceinline__ void mainloop(f32x4 (&acc)[2 * FM][FN], uint16_t* smem, const uint16_t* __restrict__ A,
                                          const uint16_t* __restrict__ Bbase, int K, const WorkItem& w, int wave, int lane,
                                          int nfrag) {
-    constexpr int A_PER_WAVE = Tile<FM>::A_PER_WAVE, N_DMA = Loader<FM>::N_DMA;
+    constexpr int N_DMA = Loader<FM>::N_DMA;
     const int wave_m = wave / WN, wave_n = wave % WN;
     Loader<FM> ld;
     ld.Abase = A + (size_t)w.row0 * K;
